@@ -1,0 +1,119 @@
+/*
+ * mixquant.h -- C ABI of the MI355X (gfx950) library for the prefill linear layer of
+ * Mix-Quant run as NVFP4 W4A4 (Section 3.3, "NVFP4 Microscaling Quantization for
+ * Prefilling"): on-the-fly activation quantization (Eq. 2 then Eq. 1) followed by a
+ * block-scaled FP4 GEMM against offline-quantized weights, plus a plain BF16 GEMM that
+ * stands for the high-precision decode path the paper compares against.
+ *
+ * Conventions shared by every entry point
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *    allocates, frees or keeps a pointer, and never synchronises: each call enqueues its
+ *    kernels on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *    returns.  Calls on one stream execute in order.
+ *  - Tensor-level scales (alpha in Eq. 1) are read from device memory, so a scale computed
+ *    on the device needs no host round trip.
+ *  - Return value: MQ_OK, or an mq_status error.  Arguments are validated on the host before
+ *    anything is launched; on error nothing has been enqueued.  MQ_ERR_HIP means the HIP
+ *    runtime refused a launch; mq_last_hip_error() returns its hipError_t.
+ *  - Outputs must not overlap inputs.
+ *
+ * NVFP4 tensor (Section 3.3): a [rows, K] matrix whose contraction index K is contiguous
+ * ("layouts aligned with the GEMM dimension"), K % 16 == 0, stored as
+ *    codes  : uint8 [rows, K/2]   element k of a row in byte k/2, even k in the low nibble;
+ *                                 a code is E2M1: bit3 sign, bits2..1 exponent (bias 1),
+ *                                 bit0 mantissa -> {0, .5, 1, 1.5, 2, 3, 4, 6}
+ *    scales : uint8 [rows, K/16]  one FP8 E4M3 (OCP, max 448, no infinity) byte per block of
+ *                                 g = 16 consecutive K elements
+ *    alpha  : one float           the tensor-level scale
+ * with value x_hat[r, k] = alpha * E4M3(scales[r, k/16]) * E2M1(code[r, k])   (Eq. 1, right).
+ */
+#ifndef MIXQUANT_H
+#define MIXQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MQ_OK = 0,
+    MQ_ERR_NULL = 1,   /* a required pointer is NULL */
+    MQ_ERR_SHAPE = 2,  /* rows/M/N < 0, K <= 0, K % 16 != 0, a leading dimension too small */
+    MQ_ERR_ALIGN = 3,  /* a pointer or leading dimension breaks the stated alignment */
+    MQ_ERR_ARG = 4,    /* unknown enum value */
+    MQ_ERR_HIP = 5     /* kernel launch failed; see mq_last_hip_error() */
+} mq_status;
+
+typedef enum {
+    MQ_OUT_BF16 = 0,   /* product path: FP32 accumulator rounded to BF16 (nearest even) */
+    MQ_OUT_FP32 = 1    /* test path: the scaled FP32 accumulator itself */
+} mq_out;
+
+/* Sizes, in bytes, of the two byte arrays of an NVFP4 tensor (0 when K % 16 != 0). */
+size_t mq_codes_bytes(int64_t rows, int64_t K);
+size_t mq_scales_bytes(int64_t rows, int64_t K);
+
+/*
+ * Tensor-level scale (Section 3.3: the scale that "controls the global dynamic range"; the
+ * paper gives no formula, the workloads use alpha = max|x| / (6 * 448)).
+ * Writes alpha = max|x| / 2688 to *alpha_dev (1.0f when the tensor is all zero), all in
+ * binary32.  x_bf16: [rows, K] BF16, row stride ldx elements (ldx >= K).  K % 16 == 0,
+ * x_bf16 16-byte aligned, ldx % 8 == 0.  rows == 0 writes 1.0f.
+ */
+int nvfp4_global_scale(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
+                       float *alpha_dev, void *stream);
+
+/*
+ * NVFP4 quantizer for activations (per prefill batch) or weights (once, offline):
+ * Eq. 2 gives each block's E4M3 scale from its largest magnitude, Eq. 1 the E2M1 codes.
+ * Arithmetic, every step IEEE binary32, nearest-even, unfused, per block b of 16 elements:
+ *    s = amax_b / (6 * alpha);  sigma_b = Pi_E4M3(s)   (ties to even, saturating at 448)
+ *    r = 1 / (alpha * sigma_b); q_i = Pi_FP4(x_i * r)  (ties to even, clipped to +-6);
+ *    sigma_b == 0 gives signed-zero codes.
+ * x_bf16: [rows, K] BF16, row stride ldx elements; *alpha_dev finite and > 0, read on the
+ * device.  codes: [rows, K/2], scales: [rows, K/16], dense.  Inputs must be finite (Inf
+ * saturates, NaN gives unspecified codes; never a fault).
+ * K % 16 == 0; x_bf16 and codes 16-byte aligned; ldx % 8 == 0.  rows == 0 is a no-op.
+ */
+int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
+                   const float *alpha_dev, uint8_t *codes, uint8_t *scales, void *stream);
+
+/*
+ * Block-scaled FP4 GEMM (Section 3.3; the W4A4 linear layer of the prefill path):
+ *    Y[m, n] = alpha_a * alpha_b * sum_k  sa[m, k/16] * qa[m, k] * sb[n, k/16] * qb[n, k]
+ * A = quantized activations [M, K], B = quantized weights [N, K], both NVFP4 tensors as
+ * described above.  Every product is formed exactly, sums are accumulated in FP32, the two
+ * tensor-level scales are applied once to the accumulator, and the result is written as
+ * BF16 (nearest even) or FP32.  y: [M, N], row stride ldy elements (ldy >= N).
+ * K % 16 == 0; code arrays 16-byte aligned, scale arrays 4-byte aligned when K % 64 == 0;
+ * y 16-byte aligned and ldy % 8 == 0 for BF16 (ldy % 4 == 0 for FP32).  M, N >= 0 arbitrary
+ * (ragged batches); M == 0 or N == 0 is a no-op.  Results are bit-identical from run to run.
+ */
+int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+               const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev,
+               int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream);
+
+/*
+ * High-precision baseline (the BF16 path that decoding keeps and that the paper's prefill
+ * speed-up is measured against): Y = X . W^T, X [M, K] and W [N, K] BF16 with row strides
+ * ldx, ldw elements, FP32 accumulation, output as in nvfp4_gemm.
+ * K % 8 == 0; x, w 16-byte aligned; ldx % 8 == 0, ldw % 8 == 0; y as in nvfp4_gemm.
+ */
+int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw,
+              int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream);
+
+/* Human-readable name of an mq_status value (static storage). */
+const char *mq_status_string(int status);
+
+/* hipError_t of the most recent failed launch on the calling thread (0 if none). */
+int mq_last_hip_error(void);
+
+/* Library version, "major.minor". */
+const char *mq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXQUANT_H */

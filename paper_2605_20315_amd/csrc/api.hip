@@ -1,0 +1,140 @@
+// extern "C" entry points of libmixquant: argument validation on the host, then one or a
+// few kernel launches on the caller's stream.  Nothing here allocates or synchronises.
+#include "mq_common.h"
+
+namespace mq {
+
+static thread_local int g_last_hip_error = 0;
+
+int note_launch(hipError_t e)
+{
+    if (e == hipSuccess) return MQ_OK;
+    g_last_hip_error = (int)e;
+    return MQ_ERR_HIP;
+}
+
+static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+}  // namespace mq
+
+using namespace mq;
+
+extern "C" {
+
+size_t mq_codes_bytes(int64_t rows, int64_t K)
+{
+    if (rows < 0 || K <= 0 || K % kBlock != 0) return 0;
+    return (size_t)rows * (size_t)(K / 2);
+}
+
+size_t mq_scales_bytes(int64_t rows, int64_t K)
+{
+    if (rows < 0 || K <= 0 || K % kBlock != 0) return 0;
+    return (size_t)rows * (size_t)(K / kBlock);
+}
+
+int nvfp4_global_scale(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, float *alpha_dev,
+                       void *stream)
+{
+    if (!alpha_dev || (!x_bf16 && rows > 0)) return MQ_ERR_NULL;
+    if (rows < 0 || K <= 0 || K % kBlock != 0 || ldx < K) return MQ_ERR_SHAPE;
+    if (!aligned(x_bf16, 16) || ldx % 8 != 0 || !aligned(alpha_dev, 4)) return MQ_ERR_ALIGN;
+    return launch_global_scale(static_cast<const uint16_t *>(x_bf16), rows, K, ldx, alpha_dev,
+                               static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, const float *alpha_dev,
+                   uint8_t *codes, uint8_t *scales, void *stream)
+{
+    if (rows < 0 || K <= 0 || K % kBlock != 0 || ldx < K) return MQ_ERR_SHAPE;
+    if (rows == 0) return MQ_OK;
+    if (!x_bf16 || !alpha_dev || !codes || !scales) return MQ_ERR_NULL;
+    if (!aligned(x_bf16, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(alpha_dev, 4))
+        return MQ_ERR_ALIGN;
+    return launch_quantize(static_cast<const uint16_t *>(x_bf16), rows, K, ldx, alpha_dev, codes, scales,
+                           static_cast<hipStream_t>(stream));
+}
+
+static int check_out(const void *y, int64_t N, int64_t ldy, int out)
+{
+    if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
+    if (ldy < N) return MQ_ERR_SHAPE;
+    if (!aligned(y, 16)) return MQ_ERR_ALIGN;
+    if (ldy % (out == MQ_OUT_BF16 ? 8 : 4) != 0) return MQ_ERR_ALIGN;
+    return MQ_OK;
+}
+
+int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+               const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
+               int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream)
+{
+    if (M < 0 || N < 0 || K <= 0 || K % kBlock != 0) return MQ_ERR_SHAPE;
+    if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
+    if (M == 0 || N == 0) return MQ_OK;
+    if (!a_codes || !a_scales || !a_alpha_dev || !b_codes || !b_scales || !b_alpha_dev || !y)
+        return MQ_ERR_NULL;
+    int rc = check_out(y, N, ldy, out);
+    if (rc != MQ_OK) return rc;
+    if (!aligned(a_codes, 16) || !aligned(b_codes, 16) || !aligned(a_alpha_dev, 4) ||
+        !aligned(b_alpha_dev, 4))
+        return MQ_ERR_ALIGN;
+    if (K % 64 == 0 && (!aligned(a_scales, 4) || !aligned(b_scales, 4))) return MQ_ERR_ALIGN;
+    GemmArgs g{};
+    g.a = a_codes;
+    g.b = b_codes;
+    g.a_scales = a_scales;
+    g.b_scales = b_scales;
+    g.a_alpha = a_alpha_dev;
+    g.b_alpha = b_alpha_dev;
+    g.lda = g.ldb = K;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.y = y;
+    g.ldy = ldy;
+    g.out = out;
+    return launch_gemm_fp4(g, static_cast<hipStream_t>(stream));
+}
+
+int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw, int64_t M, int64_t N,
+              int64_t K, void *y, int64_t ldy, int out, void *stream)
+{
+    if (M < 0 || N < 0 || K <= 0 || K % 8 != 0 || ldx < K || ldw < K) return MQ_ERR_SHAPE;
+    if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
+    if (M == 0 || N == 0) return MQ_OK;
+    if (!x_bf16 || !w_bf16 || !y) return MQ_ERR_NULL;
+    int rc = check_out(y, N, ldy, out);
+    if (rc != MQ_OK) return rc;
+    if (!aligned(x_bf16, 16) || !aligned(w_bf16, 16) || ldx % 8 != 0 || ldw % 8 != 0) return MQ_ERR_ALIGN;
+    GemmArgs g{};
+    g.a = x_bf16;
+    g.b = w_bf16;
+    g.lda = ldx;
+    g.ldb = ldw;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.y = y;
+    g.ldy = ldy;
+    g.out = out;
+    return launch_gemm_bf16(g, static_cast<hipStream_t>(stream));
+}
+
+const char *mq_status_string(int status)
+{
+    switch (status) {
+    case MQ_OK: return "MQ_OK";
+    case MQ_ERR_NULL: return "MQ_ERR_NULL: a required pointer is NULL";
+    case MQ_ERR_SHAPE: return "MQ_ERR_SHAPE: bad extent (K must be a positive multiple of 16, ld >= extent)";
+    case MQ_ERR_ALIGN: return "MQ_ERR_ALIGN: pointer or leading dimension breaks the required alignment";
+    case MQ_ERR_ARG: return "MQ_ERR_ARG: unknown enum value";
+    case MQ_ERR_HIP: return "MQ_ERR_HIP: kernel launch failed (see mq_last_hip_error)";
+    default: return "unknown mq_status";
+    }
+}
+
+int mq_last_hip_error(void) { return g_last_hip_error; }
+
+const char *mq_version(void) { return "0.1"; }
+
+}  // extern "C"

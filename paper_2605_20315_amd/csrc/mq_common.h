@@ -1,0 +1,47 @@
+// Shared declarations of the HIP library (gfx950 only).  Internal; the public C ABI is
+// include/mixquant.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mixquant.h"
+
+namespace mq {
+
+constexpr int kBlock = 16;  // g: elements per NVFP4 scale block (Section 3.3)
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// Records a failed launch for mq_last_hip_error() and maps it to MQ_ERR_HIP.
+int note_launch(hipError_t e);
+
+// quantize.hip
+int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, float *alpha,
+                        hipStream_t s);
+int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
+                    uint8_t *codes, uint8_t *scales, hipStream_t s);
+
+// gemm.hip
+struct GemmArgs {
+    // NVFP4 operands (fp4 == true) or BF16 operands (fp4 == false, *_codes hold the BF16 data)
+    const void *a;            // [M, K] codes or BF16
+    const void *b;            // [N, K] codes or BF16
+    const uint8_t *a_scales;  // [M, K/16]
+    const uint8_t *b_scales;  // [N, K/16]
+    const float *a_alpha;     // device scalars (NVFP4 only)
+    const float *b_alpha;
+    int64_t lda, ldb;         // BF16 row strides in elements (NVFP4 operands are dense)
+    int64_t M, N, K;
+    void *y;
+    int64_t ldy;
+    int out;                  // mq_out
+};
+int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);
+int launch_gemm_bf16(const GemmArgs &g, hipStream_t s);
+
+}  // namespace mq

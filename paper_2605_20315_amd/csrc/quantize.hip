@@ -1,0 +1,172 @@
+// NVFP4 quantizer kernels for gfx950: Eq. 2 (block scale) then Eq. 1 (element codes) of
+// Section 3.3, plus the amax-based tensor-level scale.
+//
+// The quantizer is HBM-bound: per element it reads 2 bytes (BF16) and writes 0.5 byte of
+// codes and 1/16 byte of scale.  One lane owns one 16-element block: two 128-bit loads, a
+// packed 16-bit integer max for the block amax (|x| of a BF16 is its low 15 bits, and for
+// non-NaN values integer order equals magnitude order), two IEEE binary32 divisions per
+// block, then one multiply per element and one hardware FP32->FP4 pack per element pair.
+//
+// Hardware conversions used, with the behaviour measured on gfx950:
+//   v_cvt_pk_fp8_f32           OCP E4M3, nearest-even, gradual underflow; overflow gives the
+//                              NaN byte, so the argument is clamped to 448 first (exact).
+//   v_cvt_pk_f32_fp8           exact decode of all 256 bytes.
+//   v_cvt_scalef32_pk_fp4_f32  nearest-even onto the E2M1 grid, clips to +-6, keeps the sign
+//                              of zero; first source -> low nibble, second -> high nibble of
+//                              the selected byte; only the exponent of its scale operand is
+//                              used, so the scale is passed as 1.0 and the multiply by
+//                              1/(alpha*sigma) is done beforehand in FP32.
+#include "mq_common.h"
+
+namespace mq {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ uint32_t amax16_bits(uint4 v0, uint4 v1)
+{
+    const uint32_t m = 0x7FFF7FFFu;
+    u16x2 a = __builtin_bit_cast(u16x2, v0.x & m);
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v0.y & m));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v0.z & m));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v0.w & m));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v1.x & m));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v1.y & m));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v1.z & m));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v1.w & m));
+    uint32_t lo = a[0], hi = a[1];
+    return lo > hi ? lo : hi;
+}
+
+// Two BF16 in one dword (element 2i low, 2i+1 high) -> one byte of two E2M1 codes written
+// into byte `SEL` of `packed`.
+template <int SEL>
+__device__ __forceinline__ uint32_t pack_pair(uint32_t packed, uint32_t w, float r)
+{
+    float y0 = __uint_as_float(w << 16) * r;          // Eq. 1 argument, element 2i
+    float y1 = __uint_as_float(w & 0xFFFF0000u) * r;  // element 2i+1
+    return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, y0, y1, 1.0f, SEL);
+}
+
+// One lane per 16-element block.  CONTIG: ldx == K, so block g starts at element 16*g.
+template <bool CONTIG>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__restrict__ x,
+                                                            int64_t total_blocks, int blocks_per_row,
+                                                            int64_t ldx,
+                                                            const float *__restrict__ alpha_p,
+                                                            uint8_t *__restrict__ codes,
+                                                            uint8_t *__restrict__ scales)
+{
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= total_blocks) return;
+    const float alpha = *alpha_p;
+    const float d6 = 6.0f * alpha;  // alpha * q_max
+    const uint16_t *src;
+    if (CONTIG) {
+        src = x + g * kBlock;
+    } else {
+        const int64_t row = g / blocks_per_row;
+        const int64_t b = g - row * blocks_per_row;
+        src = x + row * ldx + b * kBlock;
+    }
+    const uint4 v0 = reinterpret_cast<const uint4 *>(src)[0];
+    const uint4 v1 = reinterpret_cast<const uint4 *>(src)[1];
+
+    const float amax = __uint_as_float(amax16_bits(v0, v1) << 16);
+    float s = amax / d6;                                     // Eq. 2 argument (IEEE division)
+    s = fminf(s, 448.0f);                                    // saturation of Pi_E4M3
+    const int sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;  // Pi_E4M3
+    const float sigma = __builtin_amdgcn_cvt_pk_f32_fp8(sb, false)[0];
+    const float t = alpha * sigma;
+    const float r = (sigma == 0.0f) ? 0.0f : 1.0f / t;       // IEEE division
+
+    uint32_t c0 = 0, c1 = 0;
+    c0 = pack_pair<0>(c0, v0.x, r);
+    c0 = pack_pair<1>(c0, v0.y, r);
+    c0 = pack_pair<2>(c0, v0.z, r);
+    c0 = pack_pair<3>(c0, v0.w, r);
+    c1 = pack_pair<0>(c1, v1.x, r);
+    c1 = pack_pair<1>(c1, v1.y, r);
+    c1 = pack_pair<2>(c1, v1.z, r);
+    c1 = pack_pair<3>(c1, v1.w, r);
+
+    reinterpret_cast<uint2 *>(codes)[g] = make_uint2(c0, c1);  // dense [rows, K/2]: 8 bytes per block
+    scales[g] = (uint8_t)sb;                                   // dense [rows, K/16]
+}
+
+// ---- tensor-level scale ------------------------------------------------------------------
+
+__global__ void amax_init_kernel(uint32_t *acc) { *acc = 0u; }
+
+__global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t *__restrict__ x, int64_t rows,
+                                                        int chunks_per_row, int64_t ldx,
+                                                        uint32_t *acc)
+{
+    uint32_t m = 0;
+    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(x + row * ldx);
+        for (int c = threadIdx.x; c < chunks_per_row; c += kThreads) {
+            const uint4 v = p[c];
+            const uint32_t k = 0x7FFF7FFFu;
+            u16x2 a = __builtin_bit_cast(u16x2, v.x & k);
+            a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.y & k));
+            a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.z & k));
+            a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.w & k));
+            uint32_t lo = a[0], hi = a[1];
+            uint32_t t = lo > hi ? lo : hi;
+            m = t > m ? t : m;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        uint32_t o = __shfl_xor(m, off);
+        m = o > m ? o : m;
+    }
+    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(acc, m);
+}
+
+// *acc holds the largest |x| as BF16 bits; overwrite it with alpha = amax / (6 * 448).
+__global__ void amax_final_kernel(uint32_t *acc)
+{
+    const float amax = __uint_as_float(*acc << 16);
+    const float alpha = (amax == 0.0f) ? 1.0f : amax / 2688.0f;
+    *reinterpret_cast<float *>(acc) = alpha;
+}
+
+}  // namespace
+
+int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
+                    uint8_t *codes, uint8_t *scales, hipStream_t s)
+{
+    const int64_t bpr = K / kBlock;
+    const int64_t total = rows * bpr;
+    if (total == 0) return MQ_OK;
+    const int64_t grid = (total + kThreads - 1) / kThreads;
+    if (grid > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    if (ldx == K)
+        quantize_kernel<true><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, total, (int)bpr, ldx, alpha,
+                                                                             codes, scales);
+    else
+        quantize_kernel<false><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, total, (int)bpr, ldx, alpha,
+                                                                              codes, scales);
+    return note_launch(hipGetLastError());
+}
+
+int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, float *alpha,
+                        hipStream_t s)
+{
+    uint32_t *acc = reinterpret_cast<uint32_t *>(alpha);
+    amax_init_kernel<<<1, 1, 0, s>>>(acc);
+    int rc = note_launch(hipGetLastError());
+    if (rc != MQ_OK) return rc;
+    if (rows > 0) {
+        const int64_t grid = rows < 4096 ? rows : 4096;
+        amax_kernel<<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, rows, (int)(K / 8), ldx, acc);
+        rc = note_launch(hipGetLastError());
+        if (rc != MQ_OK) return rc;
+    }
+    amax_final_kernel<<<1, 1, 0, s>>>(acc);
+    return note_launch(hipGetLastError());
+}
+
+}  // namespace mq

@@ -1,0 +1,106 @@
+"""Thin Python binding of the C ABI in include/mixquant.h: same names, argument marshalling only.
+
+Every function takes torch tensors that live on the GPU, passes their device pointers and
+the current HIP stream to the library, and returns the output tensors.  PyTorch provides
+device memory and streams; all arithmetic runs in the HIP kernels.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import _lib
+from ._lib import MQ_OUT_BF16, MQ_OUT_FP32, MixQuantError  # noqa: F401
+
+BLOCK = 16
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _need_gpu(*tensors) -> None:
+    for t in tensors:
+        if not t.is_cuda:
+            raise MixQuantError("tensors must live on the GPU (the library has no CPU path)")
+
+
+def _rows_k_ld(x: torch.Tensor):
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise MixQuantError("expected a 2-D tensor whose last dimension is contiguous")
+    ld = x.stride(0) if x.shape[0] > 1 else max(x.stride(0), x.shape[1])
+    return x.shape[0], x.shape[1], ld
+
+
+def nvfp4_global_scale(x_bf16: torch.Tensor, alpha_out: torch.Tensor | None = None) -> torch.Tensor:
+    """alpha = max|x| / (6*448) as a one-element float32 device tensor."""
+    _need_gpu(x_bf16)
+    assert x_bf16.dtype == torch.bfloat16
+    rows, K, ld = _rows_k_ld(x_bf16)
+    alpha = alpha_out if alpha_out is not None else torch.empty(1, dtype=torch.float32, device=x_bf16.device)
+    rc = _lib.load().nvfp4_global_scale(x_bf16.data_ptr(), rows, K, ld, alpha.data_ptr(), _stream())
+    _lib.check(rc, "nvfp4_global_scale")
+    return alpha
+
+
+def nvfp4_quantize(x_bf16: torch.Tensor, alpha: torch.Tensor, codes: torch.Tensor | None = None,
+                   scales: torch.Tensor | None = None):
+    """Eq. 2 then Eq. 1 of Section 3.3.  Returns (codes uint8 [rows, K/2], scales uint8 [rows, K/16])."""
+    _need_gpu(x_bf16, alpha)
+    assert x_bf16.dtype == torch.bfloat16 and alpha.dtype == torch.float32
+    rows, K, ld = _rows_k_ld(x_bf16)
+    if K % BLOCK:
+        _lib.check(2, "nvfp4_quantize")
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=x_bf16.device)
+    if scales is None:
+        scales = torch.empty((rows, K // BLOCK), dtype=torch.uint8, device=x_bf16.device)
+    assert codes.is_contiguous() and scales.is_contiguous()
+    rc = _lib.load().nvfp4_quantize(x_bf16.data_ptr(), rows, K, ld, alpha.data_ptr(),
+                                    codes.data_ptr(), scales.data_ptr(), _stream())
+    _lib.check(rc, "nvfp4_quantize")
+    return codes, scales
+
+
+def nvfp4_gemm(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int = MQ_OUT_BF16,
+               y: torch.Tensor | None = None) -> torch.Tensor:
+    """Y[M, N] = dequant(A)[M, K] . dequant(B)[N, K]^T, FP32 accumulate, BF16 or FP32 out."""
+    _need_gpu(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha)
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    assert b_codes.shape[1] * 2 == K and a_scales.shape == (M, K // BLOCK) and b_scales.shape == (N, K // BLOCK)
+    for t in (a_codes, a_scales, b_codes, b_scales):
+        assert t.dtype == torch.uint8 and t.is_contiguous()
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16 if out == MQ_OUT_BF16 else torch.float32,
+                        device=a_codes.device)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    rc = _lib.load().nvfp4_gemm(a_codes.data_ptr(), a_scales.data_ptr(), a_alpha.data_ptr(),
+                                b_codes.data_ptr(), b_scales.data_ptr(), b_alpha.data_ptr(),
+                                M, N, K, y.data_ptr(), ldy, out, _stream())
+    _lib.check(rc, "nvfp4_gemm")
+    return y
+
+
+def bf16_gemm(x_bf16: torch.Tensor, w_bf16: torch.Tensor, out: int = MQ_OUT_BF16,
+              y: torch.Tensor | None = None) -> torch.Tensor:
+    """Y = X . W^T with BF16 inputs and FP32 accumulation (the high-precision baseline)."""
+    _need_gpu(x_bf16, w_bf16)
+    assert x_bf16.dtype == torch.bfloat16 and w_bf16.dtype == torch.bfloat16
+    M, K, ldx = _rows_k_ld(x_bf16)
+    N, K2, ldw = _rows_k_ld(w_bf16)
+    assert K == K2
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16 if out == MQ_OUT_BF16 else torch.float32,
+                        device=x_bf16.device)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    rc = _lib.load().bf16_gemm(x_bf16.data_ptr(), ldx, w_bf16.data_ptr(), ldw, M, N, K,
+                               y.data_ptr(), ldy, out, _stream())
+    _lib.check(rc, "bf16_gemm")
+    return y
+
+
+def nvfp4_linear(x_bf16: torch.Tensor, alpha_x: torch.Tensor, w_codes, w_scales, alpha_w,
+                 out: int = MQ_OUT_BF16, y: torch.Tensor | None = None, codes=None, scales=None):
+    """One prefill linear layer: quantize the activations, then the block-scaled GEMM (two library calls)."""
+    xc, xs = nvfp4_quantize(x_bf16, alpha_x, codes, scales)
+    return nvfp4_gemm(xc, xs, alpha_x, w_codes, w_scales, alpha_w, out, y)

@@ -1,0 +1,68 @@
+"""Host-side checks of the C-ABI library: it loads without a GPU, exports every function that
+include/mixquant.h declares, and its argument validation runs before any launch.  CPU only."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mixquant.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_20315_amd import _lib, build
+    if not os.path.exists(_lib.LIB_PATH):
+        build.build_library()
+    return _lib.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\b([a-z][a-z0-9_]*)\s*\([^;{]*\)\s*;", text)
+
+
+def test_header_declares_the_three_calls_of_the_path():
+    names = _declared_functions()
+    for required in ("nvfp4_quantize", "nvfp4_gemm", "bf16_gemm", "nvfp4_global_scale"):
+        assert required in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 9
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_size_helpers_and_status_strings(lib):
+    assert lib.mq_codes_bytes(8192, 4096) == 8192 * 2048
+    assert lib.mq_scales_bytes(8192, 4096) == 8192 * 256
+    assert lib.mq_codes_bytes(4, 24) == 0 and lib.mq_scales_bytes(-1, 16) == 0
+    for code in range(6):
+        assert lib.mq_status_string(code).decode().startswith("MQ_")
+    assert lib.mq_version().decode().count(".") == 1
+
+
+def test_validation_rejects_bad_arguments_before_any_launch(lib):
+    # no GPU is touched: every call below fails (or is a no-op) in host-side validation
+    assert lib.nvfp4_quantize(None, 4, 24, 24, None, None, None, None) == 2      # K % 16
+    assert lib.nvfp4_quantize(None, 4, 64, 64, None, None, None, None) == 1      # NULL
+    assert lib.nvfp4_quantize(None, 0, 64, 64, None, None, None, None) == 0      # empty: no-op
+    assert lib.nvfp4_quantize(None, -1, 64, 64, None, None, None, None) == 2
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 40, None, 8, 0, None) == 2
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 3, None) == 4
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, None) == 1
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, None) == 0
+    assert lib.bf16_gemm(None, 64, None, 64, 4, 4, 64, None, 8, 0, None) == 1
+    assert lib.bf16_gemm(None, 32, None, 64, 4, 4, 64, None, 8, 0, None) == 2
+    assert lib.nvfp4_global_scale(None, 4, 64, 64, None, None) == 1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2605_20315_amd as mq
+    with pytest.raises(mq.MixQuantError):
+        mq.bf16_gemm(torch.zeros(4, 8, dtype=torch.bfloat16), torch.zeros(4, 8, dtype=torch.bfloat16))

@@ -1,0 +1,193 @@
+"""GPU parity: nvfp4_gemm and bf16_gemm (C ABI, HIP kernels) against the CPU oracle's FP64
+product of the dequantized operands (Section 3.3).
+
+Acceptance: FP32 output |y - Y*| <= 1e-4 * ||row|| * ||col||; BF16 output within 1 BF16 ulp of
+the correct rounding of a value inside that same band around Y* (see _gpu_util.check_gemm_bf16).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_20315_amd as mq
+from paper_2605_20315_amd import workloads as wl
+
+from _gpu_util import (check_gemm_bf16, check_gemm_fp32, dev_bf16, dev_scalar, dev_u8, host_bits)
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_nvfp4(rng, rows, K, lo=0x28, hi=0x48):
+    scales = rng.integers(lo, hi, size=(rows, K // 16)).astype(np.uint8)
+    codes = rng.integers(0, 256, size=(rows, K // 2)).astype(np.uint8)
+    return codes, scales
+
+
+def _gpu_gemm(ac, asc, aa, bc, bsc, ba, out):
+    M, N = ac.shape[0], bc.shape[0]
+    ld = (N + 7) // 8 * 8                     # the row stride must be a multiple of 8 elements
+    buf = torch.empty((M, ld), dtype=torch.bfloat16 if out == mq.MQ_OUT_BF16 else torch.float32, device="cuda")
+    y = mq.nvfp4_gemm(dev_u8(ac), dev_u8(asc), dev_scalar(aa), dev_u8(bc), dev_u8(bsc), dev_scalar(ba), out,
+                      buf[:, :N])
+    torch.cuda.synchronize()
+    return y
+
+
+def _check_both(ac, asc, aa, bc, bsc, ba):
+    a = oracle.dequantize(ac, asc, aa)
+    b = oracle.dequantize(bc, bsc, ba)
+    ref = oracle.gemm_f64(a, b)
+    na, nb = oracle.row_norms(a), oracle.row_norms(b)
+    y32 = _gpu_gemm(ac, asc, aa, bc, bsc, ba, mq.MQ_OUT_FP32).cpu().numpy()
+    worst = check_gemm_fp32(y32, ref, na, nb)
+    y16 = host_bits(_gpu_gemm(ac, asc, aa, bc, bsc, ba, mq.MQ_OUT_BF16))
+    strict = check_gemm_bf16(y16, ref, na, nb)
+    return worst, strict
+
+
+def test_tiny_config_full_output():
+    cfg = wl.configs()[0]
+    x, w = wl.activation(cfg, 0), wl.weight(cfg, 0)
+    ax, aw = oracle.global_scale(x), oracle.global_scale(w)
+    xc, xs = oracle.quantize(x, ax)
+    wc, ws = oracle.quantize(w, aw)
+    worst, strict = _check_both(xc, xs, ax, wc, ws, aw)
+    assert worst < 1e-5          # exact products, FP32 accumulation only
+    assert strict > 0.999
+
+
+def test_tiny_config_end_to_end_through_the_gpu_quantizer():
+    cfg = wl.configs()[0]
+    x, w = wl.activation(cfg, 0), wl.weight(cfg, 0)
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    ax, aw = mq.nvfp4_global_scale(xd), mq.nvfp4_global_scale(wd)
+    wc, ws = mq.nvfp4_quantize(wd, aw)
+    y = mq.nvfp4_linear(xd, ax, wc, ws, aw)
+    torch.cuda.synchronize()
+    axr, awr = oracle.global_scale(x), oracle.global_scale(w)
+    a = oracle.dequantize(*oracle.quantize(x, axr), axr)
+    b = oracle.dequantize(*oracle.quantize(w, awr), awr)
+    check_gemm_bf16(host_bits(y), oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b))
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (1, 16, 64), (5, 48, 128), (31, 16, 64), (33, 80, 192), (127, 144, 256), (129, 272, 64),
+    (257, 130, 320), (300, 1000, 512), (513, 257, 1024), (64, 64, 4096),
+    (7, 16, 16), (19, 33, 48), (40, 24, 144),          # K not a multiple of 64: simple kernel
+])
+def test_ragged_shapes(M, N, K):
+    rng = np.random.default_rng(M * 131 + N * 17 + K)
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    _check_both(ac, asc, 0.013, bc, bsc, 0.0021)
+
+
+def test_large_tile_path_with_ragged_edges():
+    """Enough tiles to select the 256x256 configuration, with M and N off the tile grid."""
+    rng = np.random.default_rng(5)
+    M, N, K = 256 * 23 + 77, 256 * 23 + 40, 128
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    a = oracle.dequantize(ac, asc, 0.5)
+    b = oracle.dequantize(bc, bsc, 0.25)
+    rows = np.unique(np.concatenate([np.arange(0, M, 251), np.arange(M - 80, M), [255, 256, 257]]))
+    ref = oracle.gemm_f64(a[rows], b)
+    y32 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32)[torch.from_numpy(rows).cuda()].cpu().numpy()
+    check_gemm_fp32(y32, ref, oracle.row_norms(a[rows]), oracle.row_norms(b))
+    y16 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16)[torch.from_numpy(rows).cuda()]
+    check_gemm_bf16(host_bits(y16), ref, oracle.row_norms(a[rows]), oracle.row_norms(b))
+
+
+def test_extreme_scales_subnormal_and_saturated():
+    rng = np.random.default_rng(6)
+    M, N, K = 70, 96, 256
+    ac, asc = _rand_nvfp4(rng, M, K, 0x00, 0x7F)      # every E4M3 byte incl. subnormals and 448
+    bc, bsc = _rand_nvfp4(rng, N, K, 0x00, 0x7F)
+    a = oracle.dequantize(ac, asc, 1.0)
+    b = oracle.dequantize(bc, bsc, 1.0)
+    ref = oracle.gemm_f64(a, b)
+    y32 = _gpu_gemm(ac, asc, 1.0, bc, bsc, 1.0, mq.MQ_OUT_FP32).cpu().numpy()
+    check_gemm_fp32(y32, ref, oracle.row_norms(a), oracle.row_norms(b))
+
+
+def test_closed_forms_and_single_products():
+    K = 128
+    ones_c = np.full((40, K // 2), 0x22, dtype=np.uint8)
+    ones_s = np.full((40, K // 16), 0x38, dtype=np.uint8)
+    y = _gpu_gemm(ones_c, ones_s, 0.25, ones_c[:32], ones_s[:32], 3.0, mq.MQ_OUT_FP32).cpu().numpy()
+    assert (y == 0.25 * 3.0 * K).all()
+    # one-hot: row c of A holds code c at k = 3 + 16*c % K ... every code pair, several scale pairs
+    for sa, sb in [(0x38, 0x38), (0x01, 0x7E), (0x3D, 0x45), (0x07, 0x08), (0x7E, 0x7E)]:
+        ac = np.zeros((16, K // 2), dtype=np.uint8)
+        bc = np.zeros((16, K // 2), dtype=np.uint8)
+        ac[:, 37] = np.arange(16) << 4      # element k = 75
+        bc[:, 37] = np.arange(16) << 4
+        asc = np.full((16, K // 16), sa, dtype=np.uint8)
+        bsc = np.full((16, K // 16), sb, dtype=np.uint8)
+        y = _gpu_gemm(ac, asc, 1.0, bc, bsc, 1.0, mq.MQ_OUT_FP32).cpu().numpy().astype(np.float64)
+        ref = oracle.gemm_f64(oracle.dequantize(ac, asc, 1.0), oracle.dequantize(bc, bsc, 1.0))
+        assert np.array_equal(y, ref)       # a single exact product per output
+
+
+def test_k_position_one_hot_against_oracle():
+    """An element at every k must meet exactly its partner (catches K-permutation mistakes)."""
+    K = 192
+    ac = np.zeros((K, K // 2), dtype=np.uint8)
+    asc = np.full((K, K // 16), 0x38, dtype=np.uint8)
+    for k in range(K):
+        ac[k, k // 2] = 0x2 << (4 * (k & 1))          # A[k, k] = 1.0
+    rng = np.random.default_rng(8)
+    bc, bsc = _rand_nvfp4(rng, 48, K)
+    y = _gpu_gemm(ac, asc, 1.0, bc, bsc, 1.0, mq.MQ_OUT_FP32).cpu().numpy().astype(np.float64)
+    b = oracle.dequantize(bc, bsc, 1.0)
+    assert np.array_equal(y, b.T)                     # Y[k, n] = B_hat[n, k]
+
+
+def test_determinism_and_guard_band():
+    rng = np.random.default_rng(9)
+    M, N, K = 300, 264, 256
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    args = (dev_u8(ac), dev_u8(asc), dev_scalar(0.1), dev_u8(bc), dev_u8(bsc), dev_scalar(0.2))
+    buf = torch.full((M + 9, N + 8), -7.0, dtype=torch.bfloat16, device="cuda")
+    y = buf[:M, :N]
+    mq.nvfp4_gemm(*args, mq.MQ_OUT_BF16, y)
+    y2 = mq.nvfp4_gemm(*args, mq.MQ_OUT_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    assert (buf[M:] == -7.0).all() and (buf[:, N:] == -7.0).all()
+
+
+def test_bf16_gemm_against_oracle():
+    rng = np.random.default_rng(10)
+    for M, N, K in [(256, 1024, 1024), (77, 200, 320), (5, 16, 40), (513, 264, 64)]:
+        x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+        w = wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32))
+        a, b = oracle.bf16_to_f64(x), oracle.bf16_to_f64(w)
+        ref = oracle.gemm_f64(a, b)
+        na, nb = oracle.row_norms(a), oracle.row_norms(b)
+        y32 = mq.bf16_gemm(dev_bf16(x), dev_bf16(w), mq.MQ_OUT_FP32).cpu().numpy()
+        check_gemm_fp32(y32, ref, na, nb)
+        y16 = host_bits(mq.bf16_gemm(dev_bf16(x), dev_bf16(w), mq.MQ_OUT_BF16))
+        check_gemm_bf16(y16, ref, na, nb)
+
+
+def test_gemm_errors_and_empty():
+    from paper_2605_20315_amd import _lib
+    lib = _lib.load()
+    c = torch.zeros((4, 32), dtype=torch.uint8, device="cuda")
+    s = torch.zeros((4, 4), dtype=torch.uint8, device="cuda")
+    a = dev_scalar(1.0)
+    y = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    p = lambda t: t.data_ptr()
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 24, p(y), 8, 0, st) == 2
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 2, 0, st) == 2
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 7, st) == 4
+    assert lib.nvfp4_gemm(None, p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 0, st) == 1
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 12, 0, st) == 3
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 0, 4, 64, p(y), 8, 0, st) == 0
+    x = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
+    assert lib.bf16_gemm(p(x), 8, p(x), 8, 4, 4, 12, p(y), 8, 0, st) == 2
+    assert lib.bf16_gemm(p(x), 8, p(x), 8, 4, 4, 8, p(y), 8, 0, st) == 0
+    torch.cuda.synchronize()
