@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the NVFP4 W4A4 prefill linear path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic prefill batch of the headline
+workload (Llama-3-8B-shaped linears at M = 8192 tokens): for each of the four layers, quantize
+the BF16 activations to NVFP4 on the fly (nvfp4_quantize) and run the block-scaled GEMM against
+the offline-quantized weights (nvfp4_gemm, BF16 out).  Inputs are resident in HBM before the
+timed region; tensor-level scales and weight quantization are computed once, untimed.
+
+Prints ONE JSON line.  `value` = 2*M*N*K summed over the four layers / step time, in TFLOP/s.
+Also measured: the dominant kernel's (NVFP4 GEMM) average launch duration with HIP events on
+the launch stream (-> roofline), the quantizer's bandwidth, the in-repo BF16 GEMM on the same
+shapes (-> speed-up), and the CPU oracle on a bounded sample (-> cpu_baseline).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published dense peaks (TFLOP/s) and HBM3E bandwidth (GB/s)
+PEAK_MFMA_16BIT = 2516.6
+PEAK_MFMA_FP4 = 10066.3
+PEAK_HBM_GBS = 8000.0
+QUANT_BYTES_PER_ELT = 2.0 + 0.5 + 1.0 / 16.0   # BF16 in, 4-bit code + 1/16 scale byte out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload config id (2 = Llama-3-8B shapes, M=8192)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path is single-GPU by construction (no collectives are built); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2605_20315_amd as mq
+    from paper_2605_20315_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    cfg = wl.configs()[args.config]
+    M = cfg.M
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    # ---- inputs resident in HBM, weights quantized offline, scales calibrated once (untimed) ----
+    layers = []
+    for li, layer in enumerate(cfg.layers):
+        x_bits = wl.activation(cfg, li)
+        xd, wd = dev_bf16(x_bits), dev_bf16(wl.weight(cfg, li))
+        ax, aw = mq.nvfp4_global_scale(xd), mq.nvfp4_global_scale(wd)
+        wc, ws = mq.nvfp4_quantize(wd, aw)
+        layers.append(dict(
+            layer=layer, x=xd, w=wd, ax=ax, aw=aw, wc=wc, ws=ws,
+            xc=torch.empty((M, layer.K // 2), dtype=torch.uint8, device="cuda"),
+            xs=torch.empty((M, layer.K // 16), dtype=torch.uint8, device="cuda"),
+            y=torch.empty((M, layer.N), dtype=torch.bfloat16, device="cuda"),
+            x_bits=x_bits if layer.name in ("gate_up", "linear") else None))
+    torch.cuda.synchronize()
+    flop_step = sum(wl.layer_flops(M, L["layer"]) for L in layers)
+    quant_bytes_step = sum(QUANT_BYTES_PER_ELT * M * L["layer"].K for L in layers)
+
+    def step(events=None):
+        for L in layers:
+            if events is not None:
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                e[0].record()
+            mq.nvfp4_quantize(L["x"], L["ax"], L["xc"], L["xs"])
+            if events is not None:
+                e[1].record()
+            mq.nvfp4_gemm(L["xc"], L["xs"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"])
+            if events is not None:
+                e[2].record()
+                events.append(e)
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tflops = flop_step / (ms_per_step * 1e-3) * 1e-12
+
+    nl = len(layers)
+    q_ms = [0.0] * nl
+    g_ms = [0.0] * nl
+    for i, e in enumerate(events):
+        q_ms[i % nl] += e[0].elapsed_time(e[1]) / args.steps
+        g_ms[i % nl] += e[1].elapsed_time(e[2]) / args.steps
+    gemm_ms_step, quant_ms_step = sum(g_ms), sum(q_ms)
+    gemm_tflops = flop_step / (gemm_ms_step * 1e-3) * 1e-12
+    quant_gbs = quant_bytes_step / (quant_ms_step * 1e-3) * 1e-9
+
+    # ---- BF16 GEMM on the same shapes (the high-precision baseline) ----
+    def bf16_step():
+        for L in layers:
+            mq.bf16_gemm(L["x"], L["w"], mq.MQ_OUT_BF16, L["y"])
+    for _ in range(max(1, args.warmup // 2)):
+        bf16_step()
+    torch.cuda.synchronize()
+    b0 = time.perf_counter()
+    nb = max(3, args.steps // 2)
+    for _ in range(nb):
+        bf16_step()
+    torch.cuda.synchronize()
+    bf16_ms_step = (time.perf_counter() - b0) * 1e3 / nb
+    bf16_tflops = flop_step / (bf16_ms_step * 1e-3) * 1e-12
+
+    result = {
+        "metric": "nvfp4_prefill_gemm_tflops_quant_plus_gemm_m8192",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "nvfp4 (e2m1 x e4m3 block scales) expanded exactly to fp16 MFMA, fp32 accumulate, bf16 out",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: Llama-3-8B-shaped prefill linears (qkv, o, gate_up, down) at M={M}, "
+                               "NVFP4 W4A4, quantize+GEMM per layer", "M": M,
+                   "layers": [[L["layer"].name, L["layer"].K, L["layer"].N] for L in layers]},
+        "pct_of_fp4_mfma_peak": round(100.0 * tflops / PEAK_MFMA_FP4, 2),
+        "pct_of_16bit_mfma_peak": round(100.0 * tflops / PEAK_MFMA_16BIT, 2),
+        "x_vs_bf16_gemm": round(bf16_ms_step / ms_per_step, 3),
+        "bf16_gemm_tflops": round(bf16_tflops, 2),
+        "gemm_only_tflops": round(gemm_tflops, 2),
+        "quantizer_gbs": round(quant_gbs, 1),
+        "quantizer_pct_of_hbm_peak": round(100.0 * quant_gbs / PEAK_HBM_GBS, 1),
+        "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}
+                         for i, L in enumerate(layers)},
+        "roofline": {
+            "kernel": "nvfp4 gemm (gemm_kernel<256x256, fp4>)",
+            "bound": "mfma",
+            "achieved": round(gemm_tflops, 2),
+            "peak": PEAK_MFMA_16BIT,
+            "unit": "TFLOP/s",
+            "frac": round(gemm_tflops / PEAK_MFMA_16BIT, 4),
+            "frac_of_fp4_peak": round(gemm_tflops / PEAK_MFMA_FP4, 4),
+            "avg_launch_ms": round(gemm_ms_step / nl, 4),
+            "flop_per_launch": flop_step / nl,
+            "traffic": None,
+        },
+    }
+
+    # ---- the CPU oracle on a bounded sample of the same workload (reported baseline) ----
+    if not args.no_cpu_baseline:
+        import oracle
+        L = next(l for l in layers if l["x_bits"] is not None)
+        rows = min(args.cpu_sample_rows, M)
+        xb = L["x_bits"][:rows]
+        wc, ws = L["wc"].cpu().numpy(), L["ws"].cpu().numpy()
+        ax, aw = np.float32(L["ax"].item()), np.float32(L["aw"].item())
+        c0 = time.perf_counter()
+        xc, xs = oracle.quantize(xb, ax)
+        a = oracle.dequantize(xc, xs, ax)
+        b = oracle.dequantize(wc, ws, aw)
+        y = oracle.gemm_f64(a, b)
+        y16 = oracle.bf16_round(y)
+        c1 = time.perf_counter()
+        flop = 2.0 * rows * L["layer"].N * L["layer"].K
+        result["cpu_baseline"] = {
+            "value": round(flop / (c1 - c0) * 1e-12, 6),
+            "unit": "TFLOP/s",
+            "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "seconds": round(c1 - c0, 2),
+            "sample": f"first {rows} of {M} rows of the {L['layer'].name} layer "
+                      f"(K={L['layer'].K}, N={L['layer'].N}): quantize + dequantize + FP64 GEMM + BF16 rounding",
+        }
+        # the sample doubles as an end-of-run parity spot check of what was timed
+        got = L["y"][:rows]
+        mq.nvfp4_linear(L["x"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], L["xc"], L["xs"])
+        torch.cuda.synchronize()
+        gb = got.contiguous().view(torch.int16).cpu().numpy().view(np.uint16).astype(np.int64)
+        rb = y16.astype(np.int64)
+        ordv = lambda v: np.where(v & 0x8000, -(v & 0x7FFF), v & 0x7FFF)
+        result["parity_spot_check"] = {
+            "outputs": int(gb.size),
+            "frac_within_1_bf16_ulp_of_oracle": round(float((np.abs(ordv(gb) - ordv(rb)) <= 1).mean()), 6)}
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
