@@ -163,7 +163,7 @@ def main() -> int:
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}
                          for i, L in enumerate(layers)},
         "roofline": {
-            "kernel": "nvfp4 gemm (gemm_kernel<256x256, fp4>)",
+            "kernel": "nvfp4 gemm (gemm_fp4_pipelined<256x256x64>)",
             "bound": "mfma",
             "achieved": round(gemm_tflops, 2),
             "peak": PEAK_MFMA_16BIT,
@@ -172,7 +172,10 @@ def main() -> int:
             "frac_of_fp4_peak": round(gemm_tflops / PEAK_MFMA_FP4, 4),
             "avg_launch_ms": round(gemm_ms_step / nl, 4),
             "flop_per_launch": flop_step / nl,
-            "traffic": None,
+            # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated on a plain
+            # 1 GiB copy) + WRITE_SIZE (x1.0), averaged over the four launches of a step
+            # (profiles/nvfp4_gemm_bf16_gemm_quantizer_llama8b_m8192.md)
+            "traffic": 0.51 * 2 ** 30 if args.config == 2 else None,
         },
     }
 

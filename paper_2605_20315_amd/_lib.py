@@ -8,7 +8,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmixquant.so")
+LIB_PATH = os.environ.get("MIXQUANT_LIB") or os.path.join(_HERE, "libmixquant.so")
 
 MQ_OK = 0
 MQ_OUT_BF16, MQ_OUT_FP32 = 0, 1
