@@ -58,6 +58,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     cfg = wl.configs()[args.config]
     M = cfg.M
+    LAYOUT = mq.MQ_LAYOUT_KTILE     # K-step-major NVFP4 bytes: the layout the GEMM streams
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -68,7 +69,7 @@ def main() -> int:
         x_bits = wl.activation(cfg, li)
         xd, wd = dev_bf16(x_bits), dev_bf16(wl.weight(cfg, li))
         ax, aw = mq.nvfp4_global_scale(xd), mq.nvfp4_global_scale(wd)
-        wc, ws = mq.nvfp4_quantize(wd, aw)
+        wc, ws = mq.nvfp4_quantize(wd, aw, layout=LAYOUT)
         layers.append(dict(
             layer=layer, x=xd, w=wd, ax=ax, aw=aw, wc=wc, ws=ws,
             xc=torch.empty((M, layer.K // 2), dtype=torch.uint8, device="cuda"),
@@ -84,10 +85,10 @@ def main() -> int:
             if events is not None:
                 e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
                 e[0].record()
-            mq.nvfp4_quantize(L["x"], L["ax"], L["xc"], L["xs"])
+            mq.nvfp4_quantize(L["x"], L["ax"], L["xc"], L["xs"], LAYOUT)
             if events is not None:
                 e[1].record()
-            mq.nvfp4_gemm(L["xc"], L["xs"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"])
+            mq.nvfp4_gemm(L["xc"], L["xs"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], LAYOUT)
             if events is not None:
                 e[2].record()
                 events.append(e)
@@ -185,8 +186,9 @@ def main() -> int:
         L = next(l for l in layers if l["x_bits"] is not None)
         rows = min(args.cpu_sample_rows, M)
         xb = L["x_bits"][:rows]
-        wc, ws = L["wc"].cpu().numpy(), L["ws"].cpu().numpy()
         ax, aw = np.float32(L["ax"].item()), np.float32(L["aw"].item())
+        wc_d, ws_d = mq.nvfp4_quantize(L["w"], L["aw"])      # canonical byte order for the oracle
+        wc, ws = wc_d.cpu().numpy(), ws_d.cpu().numpy()
         c0 = time.perf_counter()
         xc, xs = oracle.quantize(xb, ax)
         a = oracle.dequantize(xc, xs, ax)
@@ -206,7 +208,7 @@ def main() -> int:
         }
         # the sample doubles as an end-of-run parity spot check of what was timed
         got = L["y"][:rows]
-        mq.nvfp4_linear(L["x"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], L["xc"], L["xs"])
+        mq.nvfp4_linear(L["x"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], L["xc"], L["xs"], LAYOUT)
         torch.cuda.synchronize()
         gb = got.contiguous().view(torch.int16).cpu().numpy().view(np.uint16).astype(np.int64)
         rb = y16.astype(np.int64)

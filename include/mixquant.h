@@ -40,7 +40,7 @@ extern "C" {
 typedef enum {
     MQ_OK = 0,
     MQ_ERR_NULL = 1,   /* a required pointer is NULL */
-    MQ_ERR_SHAPE = 2,  /* rows/M/N < 0, K <= 0, K % 16 != 0, a leading dimension too small */
+    MQ_ERR_SHAPE = 2,  /* rows/M/N < 0, K <= 0, K % 16 != 0 (K % 64 != 0 for MQ_LAYOUT_KTILE), ld too small */
     MQ_ERR_ALIGN = 3,  /* a pointer or leading dimension breaks the stated alignment */
     MQ_ERR_ARG = 4,    /* unknown enum value */
     MQ_ERR_HIP = 5     /* kernel launch failed; see mq_last_hip_error() */
@@ -50,6 +50,21 @@ typedef enum {
     MQ_OUT_BF16 = 0,   /* product path: FP32 accumulator rounded to BF16 (nearest even) */
     MQ_OUT_FP32 = 1    /* test path: the scaled FP32 accumulator itself */
 } mq_out;
+
+/*
+ * Byte order of the two arrays of an NVFP4 tensor.
+ * MQ_LAYOUT_LINEAR is the canonical order described at the top of this file.
+ * MQ_LAYOUT_KTILE (needs K % 64 == 0) stores the same bytes K-step-major, so that the 64-wide
+ * K step the GEMM consumes is contiguous over rows ("layouts aligned with the GEMM dimension",
+ * Section 3.3):
+ *    codes_ktile [(t * rows + r) * 32 + j] = codes_linear [r * (K/2)  + t * 32 + j],  j < 32
+ *    scales_ktile[(t * rows + r) * 4  + j] = scales_linear[r * (K/16) + t * 4  + j],  j < 4
+ * for K step t = 0 .. K/64 - 1.  Sizes are the same in both layouts.
+ */
+typedef enum {
+    MQ_LAYOUT_LINEAR = 0,
+    MQ_LAYOUT_KTILE = 1
+} mq_layout;
 
 /* Sizes, in bytes, of the two byte arrays of an NVFP4 tensor (0 when K % 16 != 0). */
 size_t mq_codes_bytes(int64_t rows, int64_t K);
@@ -75,10 +90,12 @@ int nvfp4_global_scale(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
  * x_bf16: [rows, K] BF16, row stride ldx elements; *alpha_dev finite and > 0, read on the
  * device.  codes: [rows, K/2], scales: [rows, K/16], dense.  Inputs must be finite (Inf
  * saturates, NaN gives unspecified codes; never a fault).
+ * layout: mq_layout of the two output arrays.
  * K % 16 == 0; x_bf16 and codes 16-byte aligned; ldx % 8 == 0.  rows == 0 is a no-op.
  */
 int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
-                   const float *alpha_dev, uint8_t *codes, uint8_t *scales, void *stream);
+                   const float *alpha_dev, uint8_t *codes, uint8_t *scales, int layout,
+                   void *stream);
 
 /*
  * Block-scaled FP4 GEMM (Section 3.3; the W4A4 linear layer of the prefill path):
@@ -90,10 +107,12 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
  * K % 16 == 0; code arrays 16-byte aligned, scale arrays 4-byte aligned when K % 64 == 0;
  * y 16-byte aligned and ldy % 8 == 0 for BF16 (ldy % 4 == 0 for FP32).  M, N >= 0 arbitrary
  * (ragged batches); M == 0 or N == 0 is a no-op.  Results are bit-identical from run to run.
+ * layout: mq_layout of all four operand arrays (both operands use the same one).
  */
 int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
                const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev,
-               int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream);
+               int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout,
+               void *stream);
 
 /*
  * High-precision baseline (the BF16 path that decoding keeps and that the paper's prefill

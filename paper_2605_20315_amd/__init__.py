@@ -1,6 +1,8 @@
 """MI355X-native NVFP4 W4A4 prefill linear path of Mix-Quant (Section 3.3): HIP kernels behind
 the C ABI of include/mixquant.h, with a thin torch-tensor binding in ``ops``."""
 from .ops import (  # noqa: F401
+    MQ_LAYOUT_KTILE,
+    MQ_LAYOUT_LINEAR,
     MQ_OUT_BF16,
     MQ_OUT_FP32,
     MixQuantError,

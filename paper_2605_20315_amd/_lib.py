@@ -12,6 +12,7 @@ LIB_PATH = os.environ.get("MIXQUANT_LIB") or os.path.join(_HERE, "libmixquant.so
 
 MQ_OK = 0
 MQ_OUT_BF16, MQ_OUT_FP32 = 0, 1
+MQ_LAYOUT_LINEAR, MQ_LAYOUT_KTILE = 0, 1
 
 _lib = None
 
@@ -37,9 +38,9 @@ def load() -> ctypes.CDLL:
     lib.nvfp4_global_scale.restype = ci
     lib.nvfp4_global_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     lib.nvfp4_quantize.restype = ci
-    lib.nvfp4_quantize.argtypes = [vp, i64, i64, i64, vp, vp, vp, vp]
+    lib.nvfp4_quantize.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp]
     lib.nvfp4_gemm.restype = ci
-    lib.nvfp4_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, vp]
+    lib.nvfp4_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
     lib.bf16_gemm.restype = ci
     lib.bf16_gemm.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, ci, vp]
     lib.mq_status_string.restype = ctypes.c_char_p

@@ -44,14 +44,16 @@ int nvfp4_global_scale(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
 }
 
 int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, const float *alpha_dev,
-                   uint8_t *codes, uint8_t *scales, void *stream)
+                   uint8_t *codes, uint8_t *scales, int layout, void *stream)
 {
+    if (layout != MQ_LAYOUT_LINEAR && layout != MQ_LAYOUT_KTILE) return MQ_ERR_ARG;
     if (rows < 0 || K <= 0 || K % kBlock != 0 || ldx < K) return MQ_ERR_SHAPE;
+    if (layout == MQ_LAYOUT_KTILE && K % 64 != 0) return MQ_ERR_SHAPE;
     if (rows == 0) return MQ_OK;
     if (!x_bf16 || !alpha_dev || !codes || !scales) return MQ_ERR_NULL;
     if (!aligned(x_bf16, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(alpha_dev, 4))
         return MQ_ERR_ALIGN;
-    return launch_quantize(static_cast<const uint16_t *>(x_bf16), rows, K, ldx, alpha_dev, codes, scales,
+    return launch_quantize(static_cast<const uint16_t *>(x_bf16), rows, K, ldx, alpha_dev, codes, scales, layout,
                            static_cast<hipStream_t>(stream));
 }
 
@@ -66,10 +68,12 @@ static int check_out(const void *y, int64_t N, int64_t ldy, int out)
 
 int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
                const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
-               int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream)
+               int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *stream)
 {
     if (M < 0 || N < 0 || K <= 0 || K % kBlock != 0) return MQ_ERR_SHAPE;
     if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
+    if (layout != MQ_LAYOUT_LINEAR && layout != MQ_LAYOUT_KTILE) return MQ_ERR_ARG;
+    if (layout == MQ_LAYOUT_KTILE && K % 64 != 0) return MQ_ERR_SHAPE;
     if (M == 0 || N == 0) return MQ_OK;
     if (!a_codes || !a_scales || !a_alpha_dev || !b_codes || !b_scales || !b_alpha_dev || !y)
         return MQ_ERR_NULL;
@@ -87,6 +91,21 @@ int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_a
     g.a_alpha = a_alpha_dev;
     g.b_alpha = b_alpha_dev;
     g.lda = g.ldb = K;
+    if (layout == MQ_LAYOUT_LINEAR) {
+        g.a_c_row = g.b_c_row = K / 2;
+        g.a_c_step = g.b_c_step = 32;
+        g.a_s_row = g.b_s_row = K / kBlock;
+        g.a_s_step = g.b_s_step = 4;
+    } else {
+        g.a_c_row = g.b_c_row = 32;
+        g.a_c_step = M * 32;
+        g.b_c_step = N * 32;
+        g.a_s_row = g.b_s_row = 4;
+        g.a_s_step = M * 4;
+        g.b_s_step = N * 4;
+    }
+    const int64_t lim = (int64_t)1 << 32;
+    g.fits32 = M * g.a_c_row + 64 < lim && N * g.b_c_row + 64 < lim;
     g.M = M;
     g.N = N;
     g.K = K;
@@ -111,6 +130,7 @@ int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw, 
     g.b = w_bf16;
     g.lda = ldx;
     g.ldb = ldw;
+    g.fits32 = M * ldx * 2 + 256 < ((int64_t)1 << 32) && N * ldw * 2 + 256 < ((int64_t)1 << 32);
     g.M = M;
     g.N = N;
     g.K = K;

@@ -24,7 +24,7 @@ int note_launch(hipError_t e);
 int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, float *alpha,
                         hipStream_t s);
 int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
-                    uint8_t *codes, uint8_t *scales, hipStream_t s);
+                    uint8_t *codes, uint8_t *scales, int layout, hipStream_t s);
 
 // gemm.hip
 struct GemmArgs {
@@ -36,6 +36,11 @@ struct GemmArgs {
     const float *a_alpha;     // device scalars (NVFP4 only)
     const float *b_alpha;
     int64_t lda, ldb;         // BF16 row strides in elements (NVFP4 operands are dense)
+    // NVFP4 addressing in bytes, for either layout: the 32 code bytes of (row r, K step t) start at
+    // r * c_row + t * c_step, the 4 scale bytes at r * s_row + t * s_step (a K step is 64 elements)
+    int64_t a_c_row, a_c_step, a_s_row, a_s_step;
+    int64_t b_c_row, b_c_step, b_s_row, b_s_step;
+    bool fits32;              // every per-thread byte offset fits 32 bits (else: simple kernel)
     int64_t M, N, K;
     void *y;
     int64_t ldy;

@@ -95,6 +95,50 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
     scales[g] = (uint8_t)sb;                                   // dense [rows, K/16]
 }
 
+// K-step-major output: the code and scale bytes of one 64-wide K step are contiguous over rows.
+// A wave covers 16 rows x one K step (lane l: row l/4, block l%4): it reads one full 128-byte
+// line per row and writes 512 contiguous bytes of codes and 64 of scales.  A workgroup's four
+// waves take four consecutive K steps of the same 16 rows.
+__global__ __launch_bounds__(kThreads) void quantize_ktile_kernel(const uint16_t *__restrict__ x, int64_t rows,
+                                                                  int64_t row_base, int ksteps, int64_t ldx,
+                                                                  const float *__restrict__ alpha_p,
+                                                                  uint8_t *__restrict__ codes,
+                                                                  uint8_t *__restrict__ scales)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * 4 + wave;                       // K step
+    const int64_t row = row_base + (int64_t)blockIdx.y * 16 + (lane >> 2);
+    const int blk = lane & 3;
+    if (t >= ksteps || row >= rows) return;
+    const float alpha = *alpha_p;
+    const float d6 = 6.0f * alpha;
+    const uint16_t *src = x + row * ldx + (int64_t)t * 64 + blk * kBlock;
+    const uint4 v0 = reinterpret_cast<const uint4 *>(src)[0];
+    const uint4 v1 = reinterpret_cast<const uint4 *>(src)[1];
+
+    const float amax = __uint_as_float(amax16_bits(v0, v1) << 16);
+    float s = amax / d6;
+    s = fminf(s, 448.0f);
+    const int sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;
+    const float sigma = __builtin_amdgcn_cvt_pk_f32_fp8(sb, false)[0];
+    const float tt = alpha * sigma;
+    const float r = (sigma == 0.0f) ? 0.0f : 1.0f / tt;
+
+    uint32_t c0 = 0, c1 = 0;
+    c0 = pack_pair<0>(c0, v0.x, r);
+    c0 = pack_pair<1>(c0, v0.y, r);
+    c0 = pack_pair<2>(c0, v0.z, r);
+    c0 = pack_pair<3>(c0, v0.w, r);
+    c1 = pack_pair<0>(c1, v1.x, r);
+    c1 = pack_pair<1>(c1, v1.y, r);
+    c1 = pack_pair<2>(c1, v1.z, r);
+    c1 = pack_pair<3>(c1, v1.w, r);
+
+    const int64_t slot = (int64_t)t * rows + row;               // (K step, row)
+    reinterpret_cast<uint2 *>(codes)[slot * 4 + blk] = make_uint2(c0, c1);
+    scales[slot * 4 + blk] = (uint8_t)sb;
+}
+
 // ---- tensor-level scale ------------------------------------------------------------------
 
 __global__ void amax_init_kernel(uint32_t *acc) { *acc = 0u; }
@@ -136,11 +180,23 @@ __global__ void amax_final_kernel(uint32_t *acc)
 }  // namespace
 
 int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
-                    uint8_t *codes, uint8_t *scales, hipStream_t s)
+                    uint8_t *codes, uint8_t *scales, int layout, hipStream_t s)
 {
     const int64_t bpr = K / kBlock;
     const int64_t total = rows * bpr;
     if (total == 0) return MQ_OK;
+    if (layout == MQ_LAYOUT_KTILE) {
+        const int64_t ksteps = K / 64, gy = (rows + 15) / 16;
+        // grid.y is limited to 65535: fold the excess row groups into extra launches
+        for (int64_t y0 = 0; y0 < gy; y0 += 65535) {
+            const int64_t ny = gy - y0 < 65535 ? gy - y0 : 65535;
+            quantize_ktile_kernel<<<dim3((unsigned)((ksteps + 3) / 4), (unsigned)ny), dim3(kThreads), 0, s>>>(
+                x, rows, y0 * 16, (int)ksteps, ldx, alpha, codes, scales);
+            int rc = note_launch(hipGetLastError());
+            if (rc != MQ_OK) return rc;
+        }
+        return MQ_OK;
+    }
     const int64_t grid = (total + kThreads - 1) / kThreads;
     if (grid > 0x7FFFFFFF) return MQ_ERR_SHAPE;
     if (ldx == K)

@@ -9,7 +9,8 @@ from __future__ import annotations
 import torch
 
 from . import _lib
-from ._lib import MQ_OUT_BF16, MQ_OUT_FP32, MixQuantError  # noqa: F401
+from ._lib import (MQ_LAYOUT_KTILE, MQ_LAYOUT_LINEAR, MQ_OUT_BF16, MQ_OUT_FP32,  # noqa: F401
+                   MixQuantError)
 
 BLOCK = 16
 
@@ -43,8 +44,9 @@ def nvfp4_global_scale(x_bf16: torch.Tensor, alpha_out: torch.Tensor | None = No
 
 
 def nvfp4_quantize(x_bf16: torch.Tensor, alpha: torch.Tensor, codes: torch.Tensor | None = None,
-                   scales: torch.Tensor | None = None):
-    """Eq. 2 then Eq. 1 of Section 3.3.  Returns (codes uint8 [rows, K/2], scales uint8 [rows, K/16])."""
+                   scales: torch.Tensor | None = None, layout: int = MQ_LAYOUT_LINEAR):
+    """Eq. 2 then Eq. 1 of Section 3.3.  Returns (codes uint8 [rows, K/2], scales uint8 [rows, K/16]);
+    with MQ_LAYOUT_KTILE the same two buffers hold the bytes in K-step-major order."""
     _need_gpu(x_bf16, alpha)
     assert x_bf16.dtype == torch.bfloat16 and alpha.dtype == torch.float32
     rows, K, ld = _rows_k_ld(x_bf16)
@@ -56,13 +58,13 @@ def nvfp4_quantize(x_bf16: torch.Tensor, alpha: torch.Tensor, codes: torch.Tenso
         scales = torch.empty((rows, K // BLOCK), dtype=torch.uint8, device=x_bf16.device)
     assert codes.is_contiguous() and scales.is_contiguous()
     rc = _lib.load().nvfp4_quantize(x_bf16.data_ptr(), rows, K, ld, alpha.data_ptr(),
-                                    codes.data_ptr(), scales.data_ptr(), _stream())
+                                    codes.data_ptr(), scales.data_ptr(), layout, _stream())
     _lib.check(rc, "nvfp4_quantize")
     return codes, scales
 
 
 def nvfp4_gemm(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int = MQ_OUT_BF16,
-               y: torch.Tensor | None = None) -> torch.Tensor:
+               y: torch.Tensor | None = None, layout: int = MQ_LAYOUT_LINEAR) -> torch.Tensor:
     """Y[M, N] = dequant(A)[M, K] . dequant(B)[N, K]^T, FP32 accumulate, BF16 or FP32 out."""
     _need_gpu(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha)
     M, K = a_codes.shape[0], a_codes.shape[1] * 2
@@ -76,7 +78,7 @@ def nvfp4_gemm(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int 
     ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
     rc = _lib.load().nvfp4_gemm(a_codes.data_ptr(), a_scales.data_ptr(), a_alpha.data_ptr(),
                                 b_codes.data_ptr(), b_scales.data_ptr(), b_alpha.data_ptr(),
-                                M, N, K, y.data_ptr(), ldy, out, _stream())
+                                M, N, K, y.data_ptr(), ldy, out, layout, _stream())
     _lib.check(rc, "nvfp4_gemm")
     return y
 
@@ -100,7 +102,9 @@ def bf16_gemm(x_bf16: torch.Tensor, w_bf16: torch.Tensor, out: int = MQ_OUT_BF16
 
 
 def nvfp4_linear(x_bf16: torch.Tensor, alpha_x: torch.Tensor, w_codes, w_scales, alpha_w,
-                 out: int = MQ_OUT_BF16, y: torch.Tensor | None = None, codes=None, scales=None):
-    """One prefill linear layer: quantize the activations, then the block-scaled GEMM (two library calls)."""
-    xc, xs = nvfp4_quantize(x_bf16, alpha_x, codes, scales)
-    return nvfp4_gemm(xc, xs, alpha_x, w_codes, w_scales, alpha_w, out, y)
+                 out: int = MQ_OUT_BF16, y: torch.Tensor | None = None, codes=None, scales=None,
+                 layout: int = MQ_LAYOUT_LINEAR):
+    """One prefill linear layer: quantize the activations, then the block-scaled GEMM (two library
+    calls).  `layout` is the byte order of the weight arrays and of the activation arrays produced here."""
+    xc, xs = nvfp4_quantize(x_bf16, alpha_x, codes, scales, layout)
+    return nvfp4_gemm(xc, xs, alpha_x, w_codes, w_scales, alpha_w, out, y, layout)

@@ -55,3 +55,14 @@ def check_gemm_bf16(y_bits: np.ndarray, y_ref: np.ndarray, norm_a: np.ndarray, n
     assert ok.all(), f"{(~ok).sum()} BF16 outputs outside the accepted interval"
     strict = np.abs(got - bf16_ordinal(oracle.bf16_round(y_ref))) <= 1
     return float(strict.mean())
+
+
+def to_ktile(codes: np.ndarray, scales: np.ndarray):
+    """The K-step-major byte order, from the canonical linear one, by the documented index map:
+    codes_ktile[t, r, j] = codes_linear[r, t*32 + j], scales_ktile[t, r, j] = scales_linear[r, t*4 + j]."""
+    R, half_k = codes.shape
+    T = half_k // 32
+    assert half_k % 32 == 0 and scales.shape == (R, T * 4)
+    ck = np.ascontiguousarray(codes.reshape(R, T, 32).transpose(1, 0, 2)).reshape(R, half_k)
+    sk = np.ascontiguousarray(scales.reshape(R, T, 4).transpose(1, 0, 2)).reshape(R, T * 4)
+    return ck, sk

@@ -48,14 +48,18 @@ def test_size_helpers_and_status_strings(lib):
 
 def test_validation_rejects_bad_arguments_before_any_launch(lib):
     # no GPU is touched: every call below fails (or is a no-op) in host-side validation
-    assert lib.nvfp4_quantize(None, 4, 24, 24, None, None, None, None) == 2      # K % 16
-    assert lib.nvfp4_quantize(None, 4, 64, 64, None, None, None, None) == 1      # NULL
-    assert lib.nvfp4_quantize(None, 0, 64, 64, None, None, None, None) == 0      # empty: no-op
-    assert lib.nvfp4_quantize(None, -1, 64, 64, None, None, None, None) == 2
-    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 40, None, 8, 0, None) == 2
-    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 3, None) == 4
-    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, None) == 1
-    assert lib.nvfp4_gemm(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, None) == 0
+    assert lib.nvfp4_quantize(None, 4, 24, 24, None, None, None, 0, None) == 2      # K % 16
+    assert lib.nvfp4_quantize(None, 4, 64, 64, None, None, None, 0, None) == 1      # NULL
+    assert lib.nvfp4_quantize(None, 0, 64, 64, None, None, None, 0, None) == 0      # empty: no-op
+    assert lib.nvfp4_quantize(None, -1, 64, 64, None, None, None, 0, None) == 2
+    assert lib.nvfp4_quantize(None, 4, 48, 48, None, None, None, 1, None) == 2      # KTILE needs K % 64
+    assert lib.nvfp4_quantize(None, 4, 64, 64, None, None, None, 2, None) == 4      # unknown layout
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 40, None, 8, 0, 0, None) == 2
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 3, 0, None) == 4
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 5, None) == 4
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 48, None, 8, 0, 1, None) == 2
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 0, None) == 1
+    assert lib.nvfp4_gemm(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, 0, None) == 0
     assert lib.bf16_gemm(None, 64, None, 64, 4, 4, 64, None, 8, 0, None) == 1
     assert lib.bf16_gemm(None, 32, None, 64, 4, 4, 64, None, 8, 0, None) == 2
     assert lib.nvfp4_global_scale(None, 4, 64, 64, None, None) == 1

@@ -10,7 +10,7 @@ import oracle
 import paper_2605_20315_amd as mq
 from paper_2605_20315_amd import workloads as wl
 
-from _gpu_util import check_gemm_bf16, check_gemm_fp32, dev_bf16, host_bits
+from _gpu_util import check_gemm_bf16, check_gemm_fp32, dev_bf16, host_bits, to_ktile
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -47,6 +47,15 @@ def test_config_layer(cfg_id, layer_idx):
     assert np.array_equal(xc.cpu().numpy(), xc_ref)
     assert np.array_equal(ws.cpu().numpy(), ws_ref)
     assert np.array_equal(wc.cpu().numpy(), wc_ref)
+    # the K-step-major layout the benchmark uses: same bytes, documented permutation
+    xck, xsk = mq.nvfp4_quantize(xd, ax, layout=mq.MQ_LAYOUT_KTILE)
+    wck, wsk = mq.nvfp4_quantize(wd, aw, layout=mq.MQ_LAYOUT_KTILE)
+    torch.cuda.synchronize()
+    ck_ref, sk_ref = to_ktile(xc_ref, xs_ref)
+    assert np.array_equal(xsk.cpu().numpy(), sk_ref) and np.array_equal(xck.cpu().numpy(), ck_ref)
+    ck_ref, sk_ref = to_ktile(wc_ref, ws_ref)
+    assert np.array_equal(wsk.cpu().numpy(), sk_ref) and np.array_equal(wck.cpu().numpy(), ck_ref)
+    del ck_ref, sk_ref
     # clipping invariant on the real workload: a normal, unsaturated scale puts the block's
     # largest element on +-6
     normal = (xs_ref >= 0x08) & (xs_ref < 0x7E)
@@ -64,7 +73,7 @@ def test_config_layer(cfg_id, layer_idx):
     ref = oracle.gemm_f64(a, b)
     na, nb = oracle.row_norms(a), oracle.row_norms(b)
     ridx = torch.from_numpy(rows).cuda()
-    y16 = mq.nvfp4_gemm(xc, xs, ax, wc, ws, aw, mq.MQ_OUT_BF16)
+    y16 = mq.nvfp4_gemm(xck, xsk, ax, wck, wsk, aw, mq.MQ_OUT_BF16, layout=mq.MQ_LAYOUT_KTILE)
     torch.cuda.synchronize()
     strict = check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
     del y16

@@ -12,7 +12,7 @@ import oracle
 import paper_2605_20315_amd as mq
 from paper_2605_20315_amd import workloads as wl
 
-from _gpu_util import (check_gemm_bf16, check_gemm_fp32, dev_bf16, dev_scalar, dev_u8, host_bits)
+from _gpu_util import (check_gemm_bf16, check_gemm_fp32, dev_bf16, dev_scalar, dev_u8, host_bits, to_ktile)
 
 pytestmark = pytest.mark.gpu
 
@@ -23,12 +23,19 @@ def _rand_nvfp4(rng, rows, K, lo=0x28, hi=0x48):
     return codes, scales
 
 
-def _gpu_gemm(ac, asc, aa, bc, bsc, ba, out):
+def _gpu_gemm(ac, asc, aa, bc, bsc, ba, out, layout=None):
+    """Operands are given in the canonical linear order; layout=None alternates: the K-step-major
+    layout for the BF16 output and the linear one for FP32, so both are exercised on every case."""
     M, N = ac.shape[0], bc.shape[0]
+    if layout is None:
+        layout = mq.MQ_LAYOUT_KTILE if (out == mq.MQ_OUT_BF16 and ac.shape[1] % 32 == 0) else mq.MQ_LAYOUT_LINEAR
+    if layout == mq.MQ_LAYOUT_KTILE:
+        ac, asc = to_ktile(ac, asc)
+        bc, bsc = to_ktile(bc, bsc)
     ld = (N + 7) // 8 * 8                     # the row stride must be a multiple of 8 elements
     buf = torch.empty((M, ld), dtype=torch.bfloat16 if out == mq.MQ_OUT_BF16 else torch.float32, device="cuda")
     y = mq.nvfp4_gemm(dev_u8(ac), dev_u8(asc), dev_scalar(aa), dev_u8(bc), dev_u8(bsc), dev_scalar(ba), out,
-                      buf[:, :N])
+                      buf[:, :N], layout)
     torch.cuda.synchronize()
     return y
 
@@ -61,8 +68,8 @@ def test_tiny_config_end_to_end_through_the_gpu_quantizer():
     x, w = wl.activation(cfg, 0), wl.weight(cfg, 0)
     xd, wd = dev_bf16(x), dev_bf16(w)
     ax, aw = mq.nvfp4_global_scale(xd), mq.nvfp4_global_scale(wd)
-    wc, ws = mq.nvfp4_quantize(wd, aw)
-    y = mq.nvfp4_linear(xd, ax, wc, ws, aw)
+    wc, ws = mq.nvfp4_quantize(wd, aw, layout=mq.MQ_LAYOUT_KTILE)
+    y = mq.nvfp4_linear(xd, ax, wc, ws, aw, layout=mq.MQ_LAYOUT_KTILE)
     torch.cuda.synchronize()
     axr, awr = oracle.global_scale(x), oracle.global_scale(w)
     a = oracle.dequantize(*oracle.quantize(x, axr), axr)
@@ -138,9 +145,10 @@ def test_k_position_one_hot_against_oracle():
         ac[k, k // 2] = 0x2 << (4 * (k & 1))          # A[k, k] = 1.0
     rng = np.random.default_rng(8)
     bc, bsc = _rand_nvfp4(rng, 48, K)
-    y = _gpu_gemm(ac, asc, 1.0, bc, bsc, 1.0, mq.MQ_OUT_FP32).cpu().numpy().astype(np.float64)
     b = oracle.dequantize(bc, bsc, 1.0)
-    assert np.array_equal(y, b.T)                     # Y[k, n] = B_hat[n, k]
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        y = _gpu_gemm(ac, asc, 1.0, bc, bsc, 1.0, mq.MQ_OUT_FP32, layout).cpu().numpy().astype(np.float64)
+        assert np.array_equal(y, b.T)                 # Y[k, n] = B_hat[n, k]
 
 
 def test_determinism_and_guard_band():
@@ -153,6 +161,11 @@ def test_determinism_and_guard_band():
     y = buf[:M, :N]
     mq.nvfp4_gemm(*args, mq.MQ_OUT_BF16, y)
     y2 = mq.nvfp4_gemm(*args, mq.MQ_OUT_BF16)
+    ack, ask = to_ktile(ac, asc)
+    bck, bsk = to_ktile(bc, bsc)
+    y3 = mq.nvfp4_gemm(dev_u8(ack), dev_u8(ask), args[2], dev_u8(bck), dev_u8(bsk), args[5], mq.MQ_OUT_BF16,
+                       layout=mq.MQ_LAYOUT_KTILE)
+    assert torch.equal(y3, y2)            # same summation order in both layouts
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
     assert (buf[M:] == -7.0).all() and (buf[:, N:] == -7.0).all()
@@ -181,12 +194,14 @@ def test_gemm_errors_and_empty():
     y = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     p = lambda t: t.data_ptr()
-    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 24, p(y), 8, 0, st) == 2
-    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 2, 0, st) == 2
-    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 7, st) == 4
-    assert lib.nvfp4_gemm(None, p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 0, st) == 1
-    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 12, 0, st) == 3
-    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 0, 4, 64, p(y), 8, 0, st) == 0
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 24, p(y), 8, 0, 0, st) == 2
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 2, 0, 0, st) == 2
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 7, 0, st) == 4
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 0, 3, st) == 4
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 48, p(y), 8, 0, 1, st) == 2
+    assert lib.nvfp4_gemm(None, p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 8, 0, 0, st) == 1
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 4, 4, 64, p(y), 12, 0, 0, st) == 3
+    assert lib.nvfp4_gemm(p(c), p(s), p(a), p(c), p(s), p(a), 0, 4, 64, p(y), 8, 0, 0, st) == 0
     x = torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda")
     assert lib.bf16_gemm(p(x), 8, p(x), 8, 4, 4, 12, p(y), 8, 0, st) == 2
     assert lib.bf16_gemm(p(x), 8, p(x), 8, 4, 4, 8, p(y), 8, 0, st) == 0

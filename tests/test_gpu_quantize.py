@@ -10,7 +10,7 @@ import oracle
 import paper_2605_20315_amd as mq
 from paper_2605_20315_amd import workloads as wl
 
-from _gpu_util import dev_bf16, dev_scalar
+from _gpu_util import dev_bf16, dev_scalar, to_ktile
 
 pytestmark = pytest.mark.gpu
 
@@ -33,6 +33,10 @@ def _assert_same(bits, alpha):
     c, s = _run(bits, alpha)
     assert np.array_equal(s, s_ref), f"{(s != s_ref).sum()} scale bytes differ"
     assert np.array_equal(c, c_ref), f"{(c != c_ref).sum()} code bytes differ"
+    if bits.shape[1] % 64 == 0:      # the K-step-major layout holds the same bytes, permuted
+        ck, sk = mq.nvfp4_quantize(dev_bf16(bits), dev_scalar(alpha), layout=mq.MQ_LAYOUT_KTILE)
+        ck_ref, sk_ref = to_ktile(c_ref, s_ref)
+        assert np.array_equal(sk.cpu().numpy(), sk_ref) and np.array_equal(ck.cpu().numpy(), ck_ref)
 
 
 def test_tiny_config_bit_exact_and_global_scale():
@@ -100,7 +104,8 @@ def test_all_bf16_magnitudes_with_many_scales():
 
 def test_random_tensors_many_shapes_and_strides():
     rng = np.random.default_rng(2)
-    for rows, K in [(1, 16), (3, 48), (17, 1008), (255, 4096), (300, 272), (64, 14336)]:
+    for rows, K in [(1, 16), (3, 48), (17, 1008), (255, 4096), (300, 272), (64, 14336), (1, 64), (37, 192),
+                    (16, 256), (513, 320)]:
         x = rng.standard_normal((rows, K)).astype(np.float32) * np.exp(rng.standard_normal((rows, 1))).astype(np.float32)
         bits = _bf16(x)
         _assert_same(bits, oracle.global_scale(bits))
@@ -131,6 +136,17 @@ def test_outputs_beyond_the_tensor_are_untouched_and_empty_input_is_a_noop():
     c_ref, s_ref = oracle.quantize(bits, 0.01)
     assert np.array_equal(codes[: rows * K // 2].cpu().numpy().reshape(rows, -1), c_ref)
     assert np.array_equal(scales[: rows * K // 16].cpu().numpy().reshape(rows, -1), s_ref)
+    codes.fill_(0xA5)
+    scales.fill_(0x5A)
+    K2 = 192
+    bits2 = _bf16(rng.standard_normal((rows, K2)))
+    mq.nvfp4_quantize(dev_bf16(bits2), dev_scalar(0.01), codes[: rows * K2 // 2].view(rows, K2 // 2),
+                      scales[: rows * K2 // 16].view(rows, K2 // 16), mq.MQ_LAYOUT_KTILE)
+    torch.cuda.synchronize()
+    assert (codes[rows * K2 // 2:] == 0xA5).all() and (scales[rows * K2 // 16:] == 0x5A).all()
+    ck_ref, sk_ref = to_ktile(*oracle.quantize(bits2, 0.01))
+    assert np.array_equal(codes[: rows * K2 // 2].cpu().numpy().reshape(rows, -1), ck_ref)
+    assert np.array_equal(scales[: rows * K2 // 16].cpu().numpy().reshape(rows, -1), sk_ref)
     empty = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
     c, s = mq.nvfp4_quantize(empty, dev_scalar(1.0))
     assert c.shape == (0, 32) and s.shape == (0, 4)
@@ -156,10 +172,12 @@ def test_errors_are_reported_not_launched():
     c = torch.zeros((4, 32), dtype=torch.uint8, device="cuda")
     s = torch.zeros((4, 4), dtype=torch.uint8, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
-    assert lib.nvfp4_quantize(x.data_ptr(), 4, 24, 24, a.data_ptr(), c.data_ptr(), s.data_ptr(), st) == 2
-    assert lib.nvfp4_quantize(x.data_ptr(), 4, 64, 32, a.data_ptr(), c.data_ptr(), s.data_ptr(), st) == 2
-    assert lib.nvfp4_quantize(None, 4, 64, 64, a.data_ptr(), c.data_ptr(), s.data_ptr(), st) == 1
-    assert lib.nvfp4_quantize(x.data_ptr() + 2, 3, 64, 64, a.data_ptr(), c.data_ptr(), s.data_ptr(), st) == 3
-    assert lib.nvfp4_quantize(x.data_ptr(), 4, 64, 68, a.data_ptr(), c.data_ptr(), s.data_ptr(), st) == 3
+    assert lib.nvfp4_quantize(x.data_ptr(), 4, 24, 24, a.data_ptr(), c.data_ptr(), s.data_ptr(), 0, st) == 2
+    assert lib.nvfp4_quantize(x.data_ptr(), 4, 64, 32, a.data_ptr(), c.data_ptr(), s.data_ptr(), 0, st) == 2
+    assert lib.nvfp4_quantize(None, 4, 64, 64, a.data_ptr(), c.data_ptr(), s.data_ptr(), 0, st) == 1
+    assert lib.nvfp4_quantize(x.data_ptr() + 2, 3, 64, 64, a.data_ptr(), c.data_ptr(), s.data_ptr(), 0, st) == 3
+    assert lib.nvfp4_quantize(x.data_ptr(), 4, 64, 68, a.data_ptr(), c.data_ptr(), s.data_ptr(), 0, st) == 3
+    assert lib.nvfp4_quantize(x.data_ptr(), 4, 48, 48, a.data_ptr(), c.data_ptr(), s.data_ptr(), 1, st) == 2
+    assert lib.nvfp4_quantize(x.data_ptr(), 4, 64, 64, a.data_ptr(), c.data_ptr(), s.data_ptr(), 9, st) == 4
     with pytest.raises(mq.MixQuantError):
         mq.nvfp4_quantize(torch.zeros((4, 64), dtype=torch.bfloat16), torch.ones(1))
