@@ -7,6 +7,7 @@ from .ops import (  # noqa: F401
     MQ_OUT_FP32,
     MixQuantError,
     bf16_gemm,
+    mfma_probe,
     nvfp4_gemm,
     nvfp4_global_scale,
     nvfp4_linear,

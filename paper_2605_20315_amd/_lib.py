@@ -43,6 +43,8 @@ def load() -> ctypes.CDLL:
     lib.nvfp4_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
     lib.bf16_gemm.restype = ci
     lib.bf16_gemm.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, ci, vp]
+    lib.mq_mfma_probe.restype = ci
+    lib.mq_mfma_probe.argtypes = [vp, ci, vp, ctypes.POINTER(ctypes.c_double)]
     lib.mq_status_string.restype = ctypes.c_char_p
     lib.mq_status_string.argtypes = [ci]
     lib.mq_last_hip_error.restype = ci

@@ -140,6 +140,15 @@ int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw, 
     return launch_gemm_bf16(g, static_cast<hipStream_t>(stream));
 }
 
+int mq_mfma_probe(float *scratch_dev, int iters, void *stream, double *flop_out)
+{
+    if (!scratch_dev) return MQ_ERR_NULL;
+    if (iters < 1 || iters > (1 << 20)) return MQ_ERR_SHAPE;
+    const int blocks = 256;  // one workgroup of four waves per compute unit: one wave per SIMD
+    if (flop_out) *flop_out = (double)blocks * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+    return launch_mfma_probe(scratch_dev, iters, blocks, static_cast<hipStream_t>(stream));
+}
+
 const char *mq_status_string(int status)
 {
     switch (status) {

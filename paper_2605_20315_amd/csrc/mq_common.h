@@ -48,5 +48,6 @@ struct GemmArgs {
 };
 int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);
 int launch_gemm_bf16(const GemmArgs &g, hipStream_t s);
+int launch_mfma_probe(float *out, int iters, int blocks, hipStream_t s);
 
 }  // namespace mq

@@ -108,3 +108,13 @@ def nvfp4_linear(x_bf16: torch.Tensor, alpha_x: torch.Tensor, w_codes, w_scales,
     calls).  `layout` is the byte order of the weight arrays and of the activation arrays produced here."""
     xc, xs = nvfp4_quantize(x_bf16, alpha_x, codes, scales, layout)
     return nvfp4_gemm(xc, xs, alpha_x, w_codes, w_scales, alpha_w, out, y, layout)
+
+
+def mfma_probe(iters: int = 4000) -> float:
+    """Enqueue the matrix-pipe rate probe on the current stream; returns the flop count of the launch."""
+    import ctypes
+    scratch = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flop = ctypes.c_double(0.0)
+    rc = _lib.load().mq_mfma_probe(scratch.data_ptr(), iters, _stream(), ctypes.byref(flop))
+    _lib.check(rc, "mq_mfma_probe")
+    return flop.value
