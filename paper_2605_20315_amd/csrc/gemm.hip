@@ -165,7 +165,11 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
 #pragma unroll
     for (int q = 0; q < C::NP; ++q) {
         const bool isA = q < C::PA;
-        const int r = (tid >> 1) + (isA ? q : q - C::PA) * (C::THREADS / 2);
+        // A wave stages 32 rows; its lane pairs take the even rows first, then the odd ones, so
+        // that the 8 lanes the LDS serves together on a 128-bit write (32 banks, 128 bytes per
+        // clock) hold rows with 4 different swizzle keys and hit 8 different bank groups.
+        const int idx = lane >> 1;
+        const int r = wave * 32 + (((idx & 15) << 1) | (idx >> 4)) + (isA ? q : q - C::PA) * (C::THREADS / 2);
         const int64_t total = isA ? g.M : g.N, row0 = isA ? m0 : n0;
         int64_t grow = row0 + r;
         grow = grow < total ? grow : total - 1;
