@@ -123,6 +123,32 @@ def main() -> int:
     gemm_tflops = flop_step / (gemm_ms_step * 1e-3) * 1e-12
     quant_gbs = quant_bytes_step / (quant_ms_step * 1e-3) * 1e-9
 
+    # ---- same path with the tensor-level scale computed on the fly (amax pass + quantize + GEMM) ----
+    def dyn_step():
+        for L in layers:
+            mq.nvfp4_global_scale(L["x"], L["ax_dyn"])
+            mq.nvfp4_quantize(L["x"], L["ax_dyn"], L["xc"], L["xs"], LAYOUT)
+            mq.nvfp4_gemm(L["xc"], L["xs"], L["ax_dyn"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], LAYOUT)
+    for L in layers:
+        L["ax_dyn"] = torch.empty(1, dtype=torch.float32, device="cuda")
+    for _ in range(max(1, args.warmup // 2)):
+        dyn_step()
+    torch.cuda.synchronize()
+    d0 = time.perf_counter()
+    nd = max(3, args.steps // 2)
+    for _ in range(nd):
+        dyn_step()
+    torch.cuda.synchronize()
+    dyn_ms_step = (time.perf_counter() - d0) * 1e3 / nd
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        for L in layers:
+            mq.nvfp4_global_scale(L["x"], L["ax_dyn"])
+    e1.record()
+    torch.cuda.synchronize()
+    amax_gbs = 10 * sum(2.0 * M * L["layer"].K for L in layers) / (e0.elapsed_time(e1) * 1e-3) * 1e-9
+
     # ---- BF16 GEMM on the same shapes (the high-precision baseline) ----
     def bf16_step():
         for L in layers:
@@ -170,6 +196,8 @@ def main() -> int:
         "x_vs_bf16_gemm": round(bf16_ms_step / ms_per_step, 3),
         "bf16_gemm_tflops": round(bf16_tflops, 2),
         "gemm_only_tflops": round(gemm_tflops, 2),
+        "dynamic_alpha_pipeline_tflops": round(flop_step / (dyn_ms_step * 1e-3) * 1e-12, 2),
+        "global_scale_gbs": round(amax_gbs, 1),
         "quantizer_gbs": round(quant_gbs, 1),
         "quantizer_pct_of_hbm_peak": round(100.0 * quant_gbs / PEAK_HBM_GBS, 1),
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}

@@ -98,6 +98,16 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
                    void *stream);
 
 /*
+ * Offline weight pre-pack (weights are static across requests, Section 3.3 "Prefill-Decode
+ * Disaggregation Deployment"): copy an NVFP4 tensor from one mq_layout to the other.  Pure byte
+ * permutation by the index map given at mq_layout; src and dst must not overlap.
+ * K % 64 == 0; code arrays 16-byte aligned, scale arrays 4-byte aligned; from_layout != to_layout.
+ */
+int nvfp4_relayout(const uint8_t *src_codes, const uint8_t *src_scales, uint8_t *dst_codes,
+                   uint8_t *dst_scales, int64_t rows, int64_t K, int from_layout, int to_layout,
+                   void *stream);
+
+/*
  * Block-scaled FP4 GEMM (Section 3.3; the W4A4 linear layer of the prefill path):
  *    Y[m, n] = alpha_a * alpha_b * sum_k  sa[m, k/16] * qa[m, k] * sb[n, k/16] * qb[n, k]
  * A = quantized activations [M, K], B = quantized weights [N, K], both NVFP4 tensors as

@@ -12,4 +12,5 @@ from .ops import (  # noqa: F401
     nvfp4_global_scale,
     nvfp4_linear,
     nvfp4_quantize,
+    nvfp4_relayout,
 )

@@ -39,6 +39,8 @@ def load() -> ctypes.CDLL:
     lib.nvfp4_global_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     lib.nvfp4_quantize.restype = ci
     lib.nvfp4_quantize.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp]
+    lib.nvfp4_relayout.restype = ci
+    lib.nvfp4_relayout.argtypes = [vp, vp, vp, vp, i64, i64, ci, ci, vp]
     lib.nvfp4_gemm.restype = ci
     lib.nvfp4_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
     lib.bf16_gemm.restype = ci

@@ -57,6 +57,21 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, con
                            static_cast<hipStream_t>(stream));
 }
 
+int nvfp4_relayout(const uint8_t *src_codes, const uint8_t *src_scales, uint8_t *dst_codes, uint8_t *dst_scales,
+                   int64_t rows, int64_t K, int from_layout, int to_layout, void *stream)
+{
+    if ((from_layout != MQ_LAYOUT_LINEAR && from_layout != MQ_LAYOUT_KTILE) ||
+        (to_layout != MQ_LAYOUT_LINEAR && to_layout != MQ_LAYOUT_KTILE) || from_layout == to_layout)
+        return MQ_ERR_ARG;
+    if (rows < 0 || K <= 0 || K % 64 != 0) return MQ_ERR_SHAPE;
+    if (rows == 0) return MQ_OK;
+    if (!src_codes || !src_scales || !dst_codes || !dst_scales) return MQ_ERR_NULL;
+    if (!aligned(src_codes, 16) || !aligned(dst_codes, 16) || !aligned(src_scales, 4) || !aligned(dst_scales, 4))
+        return MQ_ERR_ALIGN;
+    return launch_relayout(src_codes, src_scales, dst_codes, dst_scales, rows, K, to_layout == MQ_LAYOUT_KTILE,
+                           static_cast<hipStream_t>(stream));
+}
+
 static int check_out(const void *y, int64_t N, int64_t ldy, int out)
 {
     if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;

@@ -26,6 +26,9 @@ int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx,
 int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
                     uint8_t *codes, uint8_t *scales, int layout, hipStream_t s);
 
+int launch_relayout(const uint8_t *src_c, const uint8_t *src_s, uint8_t *dst_c, uint8_t *dst_s, int64_t rows,
+                    int64_t K, bool to_ktile, hipStream_t s);
+
 // gemm.hip
 struct GemmArgs {
     // NVFP4 operands (fp4 == true) or BF16 operands (fp4 == false, *_codes hold the BF16 data)

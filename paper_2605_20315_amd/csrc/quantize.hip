@@ -139,34 +139,79 @@ __global__ __launch_bounds__(kThreads) void quantize_ktile_kernel(const uint16_t
     scales[slot * 4 + blk] = (uint8_t)sb;
 }
 
+// Byte permutation between the two layouts of an NVFP4 tensor (offline weight pre-pack).
+// One thread moves one (row, K step) unit: 32 code bytes and 4 scale bytes.
+__global__ __launch_bounds__(kThreads) void relayout_kernel(const uint8_t *__restrict__ src_c,
+                                                            const uint8_t *__restrict__ src_s,
+                                                            uint8_t *__restrict__ dst_c, uint8_t *__restrict__ dst_s,
+                                                            int64_t rows, int64_t ksteps, bool to_ktile)
+{
+    const int64_t u = (int64_t)blockIdx.x * kThreads + threadIdx.x;  // K-step-major unit index
+    if (u >= rows * ksteps) return;
+    const int64_t t = u / rows, r = u - t * rows;
+    const int64_t lin = r * ksteps + t;                              // row-major unit index
+    const int64_t from = to_ktile ? lin : u, to = to_ktile ? u : lin;
+    const uint4 c0 = reinterpret_cast<const uint4 *>(src_c)[from * 2];
+    const uint4 c1 = reinterpret_cast<const uint4 *>(src_c)[from * 2 + 1];
+    const uint32_t sc = reinterpret_cast<const uint32_t *>(src_s)[from];
+    reinterpret_cast<uint4 *>(dst_c)[to * 2] = c0;
+    reinterpret_cast<uint4 *>(dst_c)[to * 2 + 1] = c1;
+    reinterpret_cast<uint32_t *>(dst_s)[to] = sc;
+}
+
 // ---- tensor-level scale ------------------------------------------------------------------
 
 __global__ void amax_init_kernel(uint32_t *acc) { *acc = 0u; }
 
-__global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t *__restrict__ x, int64_t rows,
-                                                        int chunks_per_row, int64_t ldx,
-                                                        uint32_t *acc)
+__device__ __forceinline__ uint32_t amax8_bits(uint4 v)
 {
+    const uint32_t k = 0x7FFF7FFFu;
+    u16x2 a = __builtin_bit_cast(u16x2, v.x & k);
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.y & k));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.z & k));
+    a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.w & k));
+    uint32_t lo = a[0], hi = a[1];
+    return lo > hi ? lo : hi;
+}
+
+// Largest |x| of the tensor as BF16 bits, folded into *acc with one atomic per wave.  Grid-stride
+// over 16-byte chunks, four independent loads in flight per thread.  CONTIG: ldx == K.
+template <bool CONTIG>
+__global__ __launch_bounds__(kThreads) void amax_kernel(const uint16_t *__restrict__ x, int64_t total_chunks,
+                                                        int chunks_per_row, int64_t ldx, uint32_t *acc)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
     uint32_t m = 0;
-    for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(x + row * ldx);
-        for (int c = threadIdx.x; c < chunks_per_row; c += kThreads) {
-            const uint4 v = p[c];
-            const uint32_t k = 0x7FFF7FFFu;
-            u16x2 a = __builtin_bit_cast(u16x2, v.x & k);
-            a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.y & k));
-            a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.z & k));
-            a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, v.w & k));
-            uint32_t lo = a[0], hi = a[1];
-            uint32_t t = lo > hi ? lo : hi;
-            m = t > m ? t : m;
-        }
+    auto addr = [&](int64_t c) -> const uint4 * {
+        if (CONTIG) return reinterpret_cast<const uint4 *>(x) + c;
+        const int64_t row = c / chunks_per_row;
+        return reinterpret_cast<const uint4 *>(x + row * ldx) + (c - row * chunks_per_row);
+    };
+    int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; c + 3 * stride < total_chunks; c += 4 * stride) {
+        const uint4 v0 = *addr(c), v1 = *addr(c + stride), v2 = *addr(c + 2 * stride), v3 = *addr(c + 3 * stride);
+        uint32_t t0 = amax8_bits(v0), t1 = amax8_bits(v1), t2 = amax8_bits(v2), t3 = amax8_bits(v3);
+        t0 = t0 > t1 ? t0 : t1;
+        t2 = t2 > t3 ? t2 : t3;
+        t0 = t0 > t2 ? t0 : t2;
+        m = m > t0 ? m : t0;
+    }
+    for (; c < total_chunks; c += stride) {
+        const uint32_t t = amax8_bits(*addr(c));
+        m = m > t ? m : t;
     }
     for (int off = 32; off > 0; off >>= 1) {
         uint32_t o = __shfl_xor(m, off);
         m = o > m ? o : m;
     }
-    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(acc, m);
+    // one atomic per workgroup: atomics on a single address serialise in L2
+    __shared__ uint32_t wave_max[kThreads / 64];
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w) m = wave_max[w] > m ? wave_max[w] : m;
+        if (m != 0) atomicMax(acc, m);
+    }
 }
 
 // *acc holds the largest |x| as BF16 bits; overwrite it with alpha = amax / (6 * 448).
@@ -208,6 +253,17 @@ int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, con
     return note_launch(hipGetLastError());
 }
 
+int launch_relayout(const uint8_t *src_c, const uint8_t *src_s, uint8_t *dst_c, uint8_t *dst_s, int64_t rows,
+                    int64_t K, bool to_ktile, hipStream_t s)
+{
+    const int64_t ksteps = K / 64, units = rows * ksteps;
+    if (units == 0) return MQ_OK;
+    const int64_t grid = (units + kThreads - 1) / kThreads;
+    if (grid > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    relayout_kernel<<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(src_c, src_s, dst_c, dst_s, rows, ksteps, to_ktile);
+    return note_launch(hipGetLastError());
+}
+
 int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, float *alpha,
                         hipStream_t s)
 {
@@ -216,8 +272,13 @@ int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx,
     int rc = note_launch(hipGetLastError());
     if (rc != MQ_OK) return rc;
     if (rows > 0) {
-        const int64_t grid = rows < 4096 ? rows : 4096;
-        amax_kernel<<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, rows, (int)(K / 8), ldx, acc);
+        const int64_t total = rows * (K / 8);
+        int64_t grid = (total + kThreads * 4 - 1) / (kThreads * 4);
+        grid = grid < 1 ? 1 : (grid > 2048 ? 2048 : grid);   // 8 workgroups per compute unit
+        if (ldx == K)
+            amax_kernel<true><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, total, (int)(K / 8), ldx, acc);
+        else
+            amax_kernel<false><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, total, (int)(K / 8), ldx, acc);
         rc = note_launch(hipGetLastError());
         if (rc != MQ_OK) return rc;
     }

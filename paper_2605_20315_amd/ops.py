@@ -63,6 +63,19 @@ def nvfp4_quantize(x_bf16: torch.Tensor, alpha: torch.Tensor, codes: torch.Tenso
     return codes, scales
 
 
+def nvfp4_relayout(codes: torch.Tensor, scales: torch.Tensor, from_layout: int, to_layout: int):
+    """Copy an NVFP4 tensor into the other byte order (offline weight pre-pack).  Returns (codes, scales)."""
+    _need_gpu(codes, scales)
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    assert codes.dtype == torch.uint8 and scales.dtype == torch.uint8
+    assert codes.is_contiguous() and scales.is_contiguous() and scales.shape == (rows, K // BLOCK)
+    oc, os_ = torch.empty_like(codes), torch.empty_like(scales)
+    rc = _lib.load().nvfp4_relayout(codes.data_ptr(), scales.data_ptr(), oc.data_ptr(), os_.data_ptr(),
+                                    rows, K, from_layout, to_layout, _stream())
+    _lib.check(rc, "nvfp4_relayout")
+    return oc, os_
+
+
 def nvfp4_gemm(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int = MQ_OUT_BF16,
                y: torch.Tensor | None = None, layout: int = MQ_LAYOUT_LINEAR) -> torch.Tensor:
     """Y[M, N] = dequant(A)[M, K] . dequant(B)[N, K]^T, FP32 accumulate, BF16 or FP32 out."""

@@ -181,3 +181,18 @@ def test_errors_are_reported_not_launched():
     assert lib.nvfp4_quantize(x.data_ptr(), 4, 64, 64, a.data_ptr(), c.data_ptr(), s.data_ptr(), 9, st) == 4
     with pytest.raises(mq.MixQuantError):
         mq.nvfp4_quantize(torch.zeros((4, 64), dtype=torch.bfloat16), torch.ones(1))
+
+
+def test_relayout_is_the_documented_permutation_and_round_trips():
+    rng = np.random.default_rng(12)
+    for rows, K in [(1, 64), (77, 192), (300, 1024), (1024, 4096)]:
+        bits = _bf16(rng.standard_normal((rows, K)))
+        c_ref, s_ref = oracle.quantize(bits, 0.01)
+        ck_ref, sk_ref = to_ktile(c_ref, s_ref)
+        cd, sd = torch.from_numpy(c_ref).cuda(), torch.from_numpy(s_ref).cuda()
+        ck, sk = mq.nvfp4_relayout(cd, sd, mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE)
+        assert np.array_equal(ck.cpu().numpy(), ck_ref) and np.array_equal(sk.cpu().numpy(), sk_ref)
+        cl, sl = mq.nvfp4_relayout(ck, sk, mq.MQ_LAYOUT_KTILE, mq.MQ_LAYOUT_LINEAR)
+        assert torch.equal(cl, cd) and torch.equal(sl, sd)
+    with pytest.raises(mq.MixQuantError):
+        mq.nvfp4_relayout(cd, sd, mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_LINEAR)
