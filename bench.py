@@ -164,6 +164,23 @@ def main() -> int:
     bf16_ms_step = (time.perf_counter() - b0) * 1e3 / nb
     bf16_tflops = flop_step / (bf16_ms_step * 1e-3) * 1e-12
 
+    # ---- decode shapes of the high-precision path: a few tokens against the same weights (HBM-bound) ----
+    decode = {}
+    w_bytes = sum(2.0 * L["layer"].N * L["layer"].K for L in layers)
+    for md in (1, 16, 64):
+        def dec_step():
+            for L in layers:
+                mq.bf16_gemm(L["x"][:md], L["w"], mq.MQ_OUT_BF16, L["y"][:md])
+        for _ in range(3):
+            dec_step()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(20):
+            dec_step()
+        g1.record()
+        torch.cuda.synchronize()
+        decode[f"M={md}"] = round(20 * w_bytes / (g0.elapsed_time(g1) * 1e-3) * 1e-9, 1)
+
     # ---- what the matrix pipe sustains on this machine for random FP16 operands (measured roof) ----
     for _ in range(3):
         mq.mfma_probe(20000)
@@ -198,6 +215,7 @@ def main() -> int:
         "gemm_only_tflops": round(gemm_tflops, 2),
         "dynamic_alpha_pipeline_tflops": round(flop_step / (dyn_ms_step * 1e-3) * 1e-12, 2),
         "global_scale_gbs": round(amax_gbs, 1),
+        "decode_bf16_gemm_weight_gbs": decode,
         "quantizer_gbs": round(quant_gbs, 1),
         "quantizer_pct_of_hbm_peak": round(100.0 * quant_gbs / PEAK_HBM_GBS, 1),
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}

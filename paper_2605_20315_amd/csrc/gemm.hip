@@ -424,6 +424,100 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
     epilogue<C, OUT_BF16>(g, acc, 1.0f, m0, n0, wm0, wn0, frow, fhalf);
 }
 
+// ---- decode-shape BF16 product (M <= 64): weight streaming, HBM-bound ---------------------------
+
+// The high-precision decode path multiplies a handful of tokens by the whole weight matrix, so
+// the time is the time to stream W once from HBM.  A workgroup of 8 waves owns 16 rows of W; wave
+// w takes the 128-wide K super-steps w, w+8, ... (together 2 KB contiguous per row and round), so
+// 8 x (N/16) waves keep enough bytes in flight without splitting K across workgroups.  A lane
+// (row r = lane%16, group g = lane/16) loads 64 contiguous bytes of W row r and of X rows
+// r, r+16, ...; four v_mfma_f32_16x16x32_bf16 per super-step and token group accumulate
+// D[W row][token]; the 8 partial sums are added in a fixed order through LDS.
+template <int MT, bool OUT_BF16>
+__global__ __launch_bounds__(512) void bf16_skinny_kernel(GemmArgs g)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    __shared__ float red[8][MT][64][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = lane & 15, grp = lane >> 4;
+    const int64_t n0 = (int64_t)blockIdx.x * 16;
+    int64_t wr = n0 + row;
+    wr = wr < g.N ? wr : g.N - 1;
+    const uint4 *wp = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.b) + wr * g.ldb + grp * 32);
+    const uint4 *xp[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        int64_t xr = t * 16 + row;
+        xr = xr < g.M ? xr : g.M - 1;
+        xp[t] = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.a) + xr * g.lda + grp * 32);
+    }
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int S = (int)(g.K / 128);  // super-steps; 16 uint4 per row each
+    auto step = [&](int s, const uint4(&w)[4], const uint4(&x)[MT][4]) {
+        (void)s;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[j]),
+                                                                 __builtin_bit_cast(bf16x8, x[t][j]), acc[t], 0, 0, 0);
+    };
+    auto load = [&](int s, uint4(&w)[4], uint4(&x)[MT][4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = wp[s * 16 + j];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[t][j] = xp[t][s * 16 + j];
+    };
+    int s = wave;
+    for (; s + 8 < S; s += 16) {  // two super-steps of loads in flight
+        uint4 w0[4], w1[4], x0[MT][4], x1[MT][4];
+        load(s, w0, x0);
+        load(s + 8, w1, x1);
+        step(s, w0, x0);
+        step(s + 8, w1, x1);
+    }
+    if (s < S) {
+        uint4 w0[4], x0[MT][4];
+        load(s, w0, x0);
+        step(s, w0, x0);
+    }
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) red[wave][t][lane][i] = acc[t][i];
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float sum = red[0][t][lane][i];
+#pragma unroll
+                for (int w = 1; w < 8; ++w) sum += red[w][t][lane][i];
+                v[i] = sum;
+            }
+            // accumulator i of a 16x16 tile: W row 4*(lane/16) + i, token lane%16
+            const int64_t m = t * 16 + row, n = n0 + 4 * grp;
+            if (m < g.M) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n + i < g.N) {
+                        if constexpr (OUT_BF16)
+                            static_cast<__bf16 *>(g.y)[m * g.ldy + n + i] = (__bf16)v[i];
+                        else
+                            static_cast<float *>(g.y)[m * g.ldy + n + i] = v[i];
+                    }
+            }
+        }
+    }
+}
+
 // ---- fallback for K not a multiple of 64: one thread per output, exact products ---------------
 
 __device__ __forceinline__ float e2m1_f32(uint32_t c)
@@ -536,6 +630,21 @@ template <bool FP4, bool OUT_BF16>
 int launch_any(const GemmArgs &g, hipStream_t s)
 {
     if (g.M == 0 || g.N == 0) return MQ_OK;
+    if constexpr (!FP4) {
+        // decode shapes: a few tokens against the whole weight matrix
+        if (g.M <= 64 && g.K % 128 == 0 && (g.N + 15) / 16 <= 0x7FFFFFFF) {
+            const dim3 grid((unsigned)((g.N + 15) / 16)), block(512);
+            if (g.M <= 16)
+                bf16_skinny_kernel<1, OUT_BF16><<<grid, block, 0, s>>>(g);
+            else if (g.M <= 32)
+                bf16_skinny_kernel<2, OUT_BF16><<<grid, block, 0, s>>>(g);
+            else if (g.M <= 48)
+                bf16_skinny_kernel<3, OUT_BF16><<<grid, block, 0, s>>>(g);
+            else
+                bf16_skinny_kernel<4, OUT_BF16><<<grid, block, 0, s>>>(g);
+            return note_launch(hipGetLastError());
+        }
+    }
     // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
     // Large tiles once they fill the 256 CUs at least twice; smaller tiles below that.

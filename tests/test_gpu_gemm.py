@@ -173,7 +173,10 @@ def test_determinism_and_guard_band():
 
 def test_bf16_gemm_against_oracle():
     rng = np.random.default_rng(10)
-    for M, N, K in [(256, 1024, 1024), (77, 200, 320), (5, 16, 40), (513, 264, 64)]:
+    for M, N, K in [(256, 1024, 1024), (77, 200, 320), (5, 16, 40), (513, 264, 64),
+                    # decode shapes (M <= 64, K % 128 == 0): the weight-streaming kernel
+                    (1, 4096, 4096), (7, 272, 128), (16, 1000, 1024), (17, 48, 384), (33, 520, 2048),
+                    (49, 16, 256), (64, 264, 14336)]:
         x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
         w = wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32))
         a, b = oracle.bf16_to_f64(x), oracle.bf16_to_f64(w)
