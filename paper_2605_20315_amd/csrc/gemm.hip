@@ -17,8 +17,8 @@
 // covered inside each wave:
 //   * a K step of 64 is four MFMA phases of 16; the fragments of phase p+1 are read from LDS
 //     into a second register set while the 16 MFMAs of phase p run;
-//   * NVFP4: the packed codes of a tile are fetched from global memory two K steps ahead into
-//     one of two register sets, and expanded to FP16 and written to the free LDS stage one
+//   * NVFP4: the packed codes of a tile are fetched from global memory three K steps ahead into
+//     one of three register sets, and expanded to FP16 and written to the free LDS stage one
 //     quarter per phase, between the MFMAs; BF16: tiles are fetched one K step ahead into
 //     registers and written to the free LDS stage over two phases;
 //   * one barrier per K step, at the start of phase 3: before it every wave has finished writing
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
         for (int j = 0; j < 4; ++j)
             wad[q][j] = (isA ? 0 : C::B_BASE) + (r * 8 + ((half * 4 + j) ^ swz_key(r))) * 16;
     }
-    Fp4Part st[2][C::NP];
+    Fp4Part st[3][C::NP];  // tile T waits in register set T % 3
     auto load_tile = [&](int t, Fp4Part(&s)[C::NP]) {
         t = t < KT ? t : KT - 1;
         const uint8_t *ac = static_cast<const uint8_t *>(g.a) + (int64_t)t * g.a_c_step;
@@ -255,19 +255,20 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
     // prologue
     load_tile(0, st[0]);
     load_tile(1, st[1]);
+    load_tile(2, st[2]);
 #pragma unroll
     for (int q = 0; q < C::NP; ++q) store_part(q, st[0][q], 0);
     store_slot(0, st[1], 1);
-    load_tile(2, st[0]);
+    load_tile(3, st[0]);
     __syncthreads();
     read_frags(0, 0, fra[0], frb[0]);
 
-    // one K step; PAR = parity of kt (stage and register-set indices must be compile-time)
-    auto kstep = [&](int kt, auto par) {
-        constexpr int PAR = decltype(par)::value;
-        constexpr int cur = PAR, nxt = PAR ^ 1;
-        Fp4Part(&s_next)[C::NP] = st[PAR ^ 1];  // tile kt+1, later refilled with tile kt+3
-        Fp4Part(&s_cur)[C::NP] = st[PAR];       // tile kt+2
+    // one K step; R = kt % 6 fixes the LDS stage (kt % 2) and the register sets (kt % 3) at compile time
+    auto kstep = [&](int kt, auto rr) {
+        constexpr int R = decltype(rr)::value;
+        constexpr int cur = R % 2, nxt = cur ^ 1;
+        Fp4Part(&s_next)[C::NP] = st[(R + 1) % 3];  // tile kt+1, later refilled with tile kt+4
+        Fp4Part(&s_cur)[C::NP] = st[(R + 2) % 3];   // tile kt+2
         // phase 0
         read_frags(cur, 1, fra[1], frb[1]);
         store_slot(1, s_next, nxt);
@@ -287,16 +288,24 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
         __syncthreads();
         read_frags(nxt, 0, fra[0], frb[0]);
         store_slot(0, s_cur, cur);
-        load_tile(kt + 3, s_next);
+        load_tile(kt + 4, s_next);
         mfmas(fra[1], frb[1]);
         sched_phase<NMFMA, NREAD, V_PART, 4, 2 * C::NP>();
     };
     int kt = 0;
-    for (; kt + 1 < KT; kt += 2) {
+    for (; kt + 5 < KT; kt += 6) {
         kstep(kt, std::integral_constant<int, 0>{});
         kstep(kt + 1, std::integral_constant<int, 1>{});
+        kstep(kt + 2, std::integral_constant<int, 2>{});
+        kstep(kt + 3, std::integral_constant<int, 3>{});
+        kstep(kt + 4, std::integral_constant<int, 4>{});
+        kstep(kt + 5, std::integral_constant<int, 5>{});
     }
     if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
+    if (kt + 1 < KT) kstep(kt + 1, std::integral_constant<int, 1>{});
+    if (kt + 2 < KT) kstep(kt + 2, std::integral_constant<int, 2>{});
+    if (kt + 3 < KT) kstep(kt + 3, std::integral_constant<int, 3>{});
+    if (kt + 4 < KT) kstep(kt + 4, std::integral_constant<int, 4>{});
 
     const float scale = (*g.a_alpha) * (*g.b_alpha);
     epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
