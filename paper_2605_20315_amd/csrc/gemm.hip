@@ -192,25 +192,25 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
             s[q].sc = *reinterpret_cast<const uint32_t *>((q < C::PA ? as : bs) + vs[q]);
         }
     };
-    auto store_part = [&](int q, Fp4Part p, int stage) {
+    // Half a part: 16 codes of one scale block -> two 16-byte chunks of FP16 in LDS.
+    auto store_half = [&](int q, int h, Fp4Part p, int stage) {
         // Pin the first use of the prefetched registers to this point of the program: without
         // it the compiler sinks cheap consumers of the loads to the loop header, right behind
-        // the loads themselves, and the wait for them lands two phases too early.
-        asm volatile("" : "+v"(p.c.x), "+v"(p.c.y), "+v"(p.c.z), "+v"(p.c.w), "+v"(p.sc));
-        const uint32_t two = p.sc >> (half * 16);
-        const uint32_t b0 = (two & 0xFFu) << 7, b1 = (two & 0xFF00u) >> 1;
-        const uint32_t s0 = b0 | (b0 << 16), s1 = b1 | (b1 << 16);
+        // the loads themselves, and the wait for them lands phases too early.
+        uint32_t c0 = h ? p.c.z : p.c.x, c1 = h ? p.c.w : p.c.y, sc = p.sc;
+        asm volatile("" : "+v"(c0), "+v"(c1), "+v"(sc));
+        const uint32_t byte = (sc >> (half * 16 + h * 8)) & 0xFFu;  // this block's E4M3 scale
+        const uint32_t b = byte << 7, s2 = b | (b << 16);           // sigma * 2^-8 as FP16, twice
         const int so = stage * (q < C::PA ? C::A_STAGE : C::B_STAGE);
-        *reinterpret_cast<uint4 *>(L + wad[q][0] + so) = expand8(p.c.x, s0);
-        *reinterpret_cast<uint4 *>(L + wad[q][1] + so) = expand8(p.c.y, s0);
-        *reinterpret_cast<uint4 *>(L + wad[q][2] + so) = expand8(p.c.z, s1);
-        *reinterpret_cast<uint4 *>(L + wad[q][3] + so) = expand8(p.c.w, s1);
+        *reinterpret_cast<uint4 *>(L + wad[q][2 * h] + so) = expand8(c0, s2);
+        *reinterpret_cast<uint4 *>(L + wad[q][2 * h + 1] + so) = expand8(c1, s2);
     };
-    // parts handled in rotating slot `slot` (0: phase 3 of the previous K step, 1..3: phases 0..2)
+    // A tile's 2*NP half-parts are spread evenly over four rotating slots
+    // (slot 0: phase 3 of the K step before, slots 1..3: phases 0..2).
     auto store_slot = [&](int slot, const Fp4Part(&s)[C::NP], int stage) {
 #pragma unroll
-        for (int q = 0; q < C::NP; ++q)
-            if (q * 4 / C::NP == slot && (q * 4) % C::NP == 0) store_part(q, s[q], stage);
+        for (int u = 0; u < 2 * C::NP; ++u)
+            if (u * 4 / (2 * C::NP) == slot) store_half(u >> 1, u & 1, s[u >> 1], stage);
     };
 
     // fragment byte addresses (stage 0): one per phase; the 32-row tiles of a wave are 4096 bytes apart
@@ -247,17 +247,15 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
     };
 
     constexpr int NMFMA = C::TM * C::TN, NREAD = C::TM + C::TN;
-    // phases 1 and 3 always expand a part (about 40 VALU instructions and 4 LDS writes);
-    // phases 0 and 2 only when a thread has four parts per tile
-    constexpr int V_PART = (40 + NMFMA - 1) / NMFMA;
-    constexpr int W_ODD = C::NP >= 4 ? 4 : 0, V_ODD = C::NP >= 4 ? V_PART : 1;
+    // every phase expands NP/2 half-parts: about 11 VALU instructions and 2 LDS writes each
+    constexpr int N_W = C::NP, N_V = (11 * C::NP + NMFMA - 1) / NMFMA;
 
     // prologue
     load_tile(0, st[0]);
     load_tile(1, st[1]);
     load_tile(2, st[2]);
 #pragma unroll
-    for (int q = 0; q < C::NP; ++q) store_part(q, st[0][q], 0);
+    for (int slot = 0; slot < 4; ++slot) store_slot(slot, st[0], 0);
     store_slot(0, st[1], 1);
     load_tile(3, st[0]);
     __syncthreads();
@@ -273,24 +271,24 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
         read_frags(cur, 1, fra[1], frb[1]);
         store_slot(1, s_next, nxt);
         mfmas(fra[0], frb[0]);
-        sched_phase<NMFMA, NREAD, V_ODD, W_ODD, 0>();
+        sched_phase<NMFMA, NREAD, N_V, N_W, 0>();
         // phase 1
         read_frags(cur, 2, fra[0], frb[0]);
         store_slot(2, s_next, nxt);
         mfmas(fra[1], frb[1]);
-        sched_phase<NMFMA, NREAD, V_PART, 4, 0>();
+        sched_phase<NMFMA, NREAD, N_V, N_W, 0>();
         // phase 2
         read_frags(cur, 3, fra[1], frb[1]);
         store_slot(3, s_next, nxt);
         mfmas(fra[0], frb[0]);
-        sched_phase<NMFMA, NREAD, V_ODD, W_ODD, 0>();
+        sched_phase<NMFMA, NREAD, N_V, N_W, 0>();
         // phase 3
         __syncthreads();
         read_frags(nxt, 0, fra[0], frb[0]);
         store_slot(0, s_cur, cur);
         load_tile(kt + 4, s_next);
         mfmas(fra[1], frb[1]);
-        sched_phase<NMFMA, NREAD, V_PART, 4, 2 * C::NP>();
+        sched_phase<NMFMA, NREAD, N_V, N_W, 2 * C::NP>();
     };
     int kt = 0;
     for (; kt + 5 < KT; kt += 6) {
