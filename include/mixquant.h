@@ -91,7 +91,8 @@ int nvfp4_global_scale(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
  * device.  codes: [rows, K/2], scales: [rows, K/16], dense.  Inputs must be finite (Inf
  * saturates, NaN gives unspecified codes; never a fault).
  * layout: mq_layout of the two output arrays.
- * K % 16 == 0; x_bf16 and codes 16-byte aligned; ldx % 8 == 0.  rows == 0 is a no-op.
+ * K % 16 == 0; x_bf16 and codes 16-byte aligned (scales 4-byte aligned for MQ_LAYOUT_KTILE);
+ * ldx % 8 == 0.  rows == 0 is a no-op.
  */
 int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
                    const float *alpha_dev, uint8_t *codes, uint8_t *scales, int layout,

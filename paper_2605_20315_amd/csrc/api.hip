@@ -53,6 +53,7 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, con
     if (!x_bf16 || !alpha_dev || !codes || !scales) return MQ_ERR_NULL;
     if (!aligned(x_bf16, 16) || ldx % 8 != 0 || !aligned(codes, 16) || !aligned(alpha_dev, 4))
         return MQ_ERR_ALIGN;
+    if (layout == MQ_LAYOUT_KTILE && !aligned(scales, 4)) return MQ_ERR_ALIGN;
     return launch_quantize(static_cast<const uint16_t *>(x_bf16), rows, K, ldx, alpha_dev, codes, scales, layout,
                            static_cast<hipStream_t>(stream));
 }

@@ -96,47 +96,62 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
 }
 
 // K-step-major output: the code and scale bytes of one 64-wide K step are contiguous over rows.
-// A wave covers 16 rows x one K step (lane l: row l/4, block l%4): it reads one full 128-byte
-// line per row and writes 512 contiguous bytes of codes and 64 of scales.  A workgroup's four
-// waves take four consecutive K steps of the same 16 rows.
+// A workgroup covers 16 rows x 16 K steps.  Reading: each wave takes four of the rows in turn,
+// 2 KB contiguous per row (lane l: K step l/4, block l%4).  The codes and scale bytes go through
+// LDS so that writing is contiguous too: per K step 16 rows x 32 code bytes = 512 bytes and
+// 16 x 4 scale bytes = 64 bytes.
 __global__ __launch_bounds__(kThreads) void quantize_ktile_kernel(const uint16_t *__restrict__ x, int64_t rows,
                                                                   int64_t row_base, int ksteps, int64_t ldx,
                                                                   const float *__restrict__ alpha_p,
                                                                   uint8_t *__restrict__ codes,
                                                                   uint8_t *__restrict__ scales)
 {
+    constexpr int T_STRIDE = 16 * 4 + 4;        // uint2 units per K step in LDS, padded against bank conflicts
+    __shared__ uint2 lc[16 * T_STRIDE];         // [K step][row][block]
+    __shared__ uint8_t ls[16][16][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = blockIdx.x * 4 + wave;                       // K step
-    const int64_t row = row_base + (int64_t)blockIdx.y * 16 + (lane >> 2);
-    const int blk = lane & 3;
-    if (t >= ksteps || row >= rows) return;
+    const int t0 = blockIdx.x * 16;
+    const int64_t r0 = row_base + (int64_t)blockIdx.y * 16;
     const float alpha = *alpha_p;
     const float d6 = 6.0f * alpha;
-    const uint16_t *src = x + row * ldx + (int64_t)t * 64 + blk * kBlock;
-    const uint4 v0 = reinterpret_cast<const uint4 *>(src)[0];
-    const uint4 v1 = reinterpret_cast<const uint4 *>(src)[1];
-
-    const float amax = __uint_as_float(amax16_bits(v0, v1) << 16);
-    float s = amax / d6;
-    s = fminf(s, 448.0f);
-    const int sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;
-    const float sigma = __builtin_amdgcn_cvt_pk_f32_fp8(sb, false)[0];
-    const float tt = alpha * sigma;
-    const float r = (sigma == 0.0f) ? 0.0f : 1.0f / tt;
-
-    uint32_t c0 = 0, c1 = 0;
-    c0 = pack_pair<0>(c0, v0.x, r);
-    c0 = pack_pair<1>(c0, v0.y, r);
-    c0 = pack_pair<2>(c0, v0.z, r);
-    c0 = pack_pair<3>(c0, v0.w, r);
-    c1 = pack_pair<0>(c1, v1.x, r);
-    c1 = pack_pair<1>(c1, v1.y, r);
-    c1 = pack_pair<2>(c1, v1.z, r);
-    c1 = pack_pair<3>(c1, v1.w, r);
-
-    const int64_t slot = (int64_t)t * rows + row;               // (K step, row)
-    reinterpret_cast<uint2 *>(codes)[slot * 4 + blk] = make_uint2(c0, c1);
-    scales[slot * 4 + blk] = (uint8_t)sb;
+    const int tl = lane >> 2, blk = lane & 3;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int rl = wave * 4 + it;
+        const int64_t row = r0 + rl;
+        if (row < rows && t0 + tl < ksteps) {
+            const uint16_t *src = x + row * ldx + (int64_t)(t0 + tl) * 64 + blk * kBlock;
+            const uint4 v0 = reinterpret_cast<const uint4 *>(src)[0];
+            const uint4 v1 = reinterpret_cast<const uint4 *>(src)[1];
+            const float amax = __uint_as_float(amax16_bits(v0, v1) << 16);
+            float s = amax / d6;
+            s = fminf(s, 448.0f);
+            const int sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;
+            const float sigma = __builtin_amdgcn_cvt_pk_f32_fp8(sb, false)[0];
+            const float tt = alpha * sigma;
+            const float r = (sigma == 0.0f) ? 0.0f : 1.0f / tt;
+            uint32_t c0 = 0, c1 = 0;
+            c0 = pack_pair<0>(c0, v0.x, r);
+            c0 = pack_pair<1>(c0, v0.y, r);
+            c0 = pack_pair<2>(c0, v0.z, r);
+            c0 = pack_pair<3>(c0, v0.w, r);
+            c1 = pack_pair<0>(c1, v1.x, r);
+            c1 = pack_pair<1>(c1, v1.y, r);
+            c1 = pack_pair<2>(c1, v1.z, r);
+            c1 = pack_pair<3>(c1, v1.w, r);
+            lc[tl * T_STRIDE + rl * 4 + blk] = make_uint2(c0, c1);
+            ls[tl][rl][blk] = (uint8_t)sb;
+        }
+    }
+    __syncthreads();
+    const int ot = threadIdx.x >> 4, orow = threadIdx.x & 15;   // output unit: (K step, row)
+    if (t0 + ot < ksteps && r0 + orow < rows) {
+        const int64_t slot = (int64_t)(t0 + ot) * rows + r0 + orow;
+        const uint2 *p = &lc[ot * T_STRIDE + orow * 4];
+        reinterpret_cast<uint4 *>(codes)[slot * 2] = make_uint4(p[0].x, p[0].y, p[1].x, p[1].y);
+        reinterpret_cast<uint4 *>(codes)[slot * 2 + 1] = make_uint4(p[2].x, p[2].y, p[3].x, p[3].y);
+        reinterpret_cast<uint32_t *>(scales)[slot] = *reinterpret_cast<const uint32_t *>(&ls[ot][orow][0]);
+    }
 }
 
 // Byte permutation between the two layouts of an NVFP4 tensor (offline weight pre-pack).
@@ -235,7 +250,7 @@ int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, con
         // grid.y is limited to 65535: fold the excess row groups into extra launches
         for (int64_t y0 = 0; y0 < gy; y0 += 65535) {
             const int64_t ny = gy - y0 < 65535 ? gy - y0 : 65535;
-            quantize_ktile_kernel<<<dim3((unsigned)((ksteps + 3) / 4), (unsigned)ny), dim3(kThreads), 0, s>>>(
+            quantize_ktile_kernel<<<dim3((unsigned)((ksteps + 15) / 16), (unsigned)ny), dim3(kThreads), 0, s>>>(
                 x, rows, y0 * 16, (int)ksteps, ldx, alpha, codes, scales);
             int rc = note_launch(hipGetLastError());
             if (rc != MQ_OK) return rc;
