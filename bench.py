@@ -164,6 +164,23 @@ def main() -> int:
     bf16_ms_step = (time.perf_counter() - b0) * 1e3 / nb
     bf16_tflops = flop_step / (bf16_ms_step * 1e-3) * 1e-12
 
+    # ---- context: the vendor library's BF16 GEMM (hipBLASLt through torch.matmul) on the same shapes ----
+    lib_tflops = None
+    try:
+        def lib_step():
+            for L in layers:
+                torch.matmul(L["x"], L["w"].t(), out=L["y"])
+        for _ in range(3):
+            lib_step()
+        torch.cuda.synchronize()
+        l0 = time.perf_counter()
+        for _ in range(nb):
+            lib_step()
+        torch.cuda.synchronize()
+        lib_tflops = flop_step / ((time.perf_counter() - l0) / nb) * 1e-12
+    except Exception as exc:  # the library path is context only; never fail the run on it
+        print(f"bench.py: torch.matmul reference skipped: {exc}", file=sys.stderr)
+
     # ---- decode shapes of the high-precision path: a few tokens against the same weights (HBM-bound) ----
     decode = {}
     w_bytes = sum(2.0 * L["layer"].N * L["layer"].K for L in layers)
@@ -212,6 +229,7 @@ def main() -> int:
         "pct_of_16bit_mfma_peak": round(100.0 * tflops / PEAK_MFMA_16BIT, 2),
         "x_vs_bf16_gemm": round(bf16_ms_step / ms_per_step, 3),
         "bf16_gemm_tflops": round(bf16_tflops, 2),
+        "vendor_library_bf16_gemm_tflops": None if lib_tflops is None else round(lib_tflops, 2),
         "gemm_only_tflops": round(gemm_tflops, 2),
         "dynamic_alpha_pipeline_tflops": round(flop_step / (dyn_ms_step * 1e-3) * 1e-12, 2),
         "global_scale_gbs": round(amax_gbs, 1),

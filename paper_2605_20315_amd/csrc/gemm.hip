@@ -26,6 +26,7 @@
 // LDS rows are 128 bytes with a bank swizzle (below); tiles are walked in an XCD-aware grouped
 // order.  Rows beyond M or N are clamped to the last valid row instead of being zero-filled:
 // they only feed outputs that the epilogue does not store.
+#include <atomic>
 #include <type_traits>
 
 #include "mq_common.h"
@@ -55,7 +56,7 @@ struct PCfg {
     // 16-bit immediate offset of the LDS instructions)
     static constexpr int A_STAGE = BM * 128, B_STAGE = BN * 128, B_BASE = 2 * A_STAGE;
     static constexpr size_t LDS_BYTES = 2ull * (A_STAGE + B_STAGE);
-    static_assert(NP == 2 || NP == 4, "staging parts must divide the four phases");
+    static_assert(NP >= 2 && NP <= 4, "a thread stages 2 to 4 half rows per tile");
     static_assert(TM >= 1 && TN >= 1 && LA >= 1 && LB >= 1, "tile too small for this wave grid");
 };
 
@@ -247,8 +248,9 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
     };
 
     constexpr int NMFMA = C::TM * C::TN, NREAD = C::TM + C::TN;
-    // every phase expands NP/2 half-parts: about 11 VALU instructions and 2 LDS writes each
-    constexpr int N_W = C::NP, N_V = (11 * C::NP + NMFMA - 1) / NMFMA;
+    // every phase expands about NP/2 half-parts: some 11 VALU instructions and 2 LDS writes each
+    constexpr int N_W = (C::NP + 1) / 2 * 2 <= NMFMA ? (C::NP + 1) / 2 * 2 : NMFMA;
+    constexpr int N_V = (11 * C::NP + NMFMA - 1) / NMFMA;
 
     // prologue
     load_tile(0, st[0]);
@@ -608,15 +610,17 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters)
 
 // ---- launchers ------------------------------------------------------------------------------
 
+// `configured` remembers that the kernel's dynamic-LDS limit has been raised.  Two threads racing
+// here both set the same attribute to the same value, which is harmless.
 template <class Kern>
 int launch_tiles(Kern kern, size_t lds_bytes, int bm, int bn, int threads, const GemmArgs &g, hipStream_t s,
-                 bool &configured)
+                 std::atomic<bool> &configured)
 {
-    if (!configured) {
+    if (!configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return note_launch(e);
-        configured = true;
+        configured.store(true, std::memory_order_release);
     }
     const int64_t tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
@@ -659,17 +663,24 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     // 256x256: 8 waves of 128x64, two per SIMD (measured 3-4 % faster than 4 waves of 128x128:
     // the second wave fills the issue slots the first leaves at barriers and waits)
     using Big = PCfg<256, 256, 2, 4>;
+    using Mid = PCfg<256, 128, 2, 2>;   // 4 waves of 128x64: for problems of one to two rounds of 256x256 tiles
     using Small = PCfg<128, 128, 2, 2>;
-    static bool cfg_big = false, cfg_small = false;
+    static std::atomic<bool> cfg_big{false}, cfg_mid{false}, cfg_small{false};
+    const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
         if (big_tiles >= 512)
             return launch_tiles(gemm_fp4_pipelined<Big, OUT_BF16>, Big::LDS_BYTES, 256, 256, Big::THREADS, g, s, cfg_big);
+        if (mid_tiles >= 256)
+            return launch_tiles(gemm_fp4_pipelined<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s, cfg_mid);
         return launch_tiles(gemm_fp4_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
                             cfg_small);
     } else {
         if (big_tiles >= 512)
             return launch_tiles(gemm_bf16_pipelined<Big, OUT_BF16>, Big::LDS_BYTES, 256, 256, Big::THREADS, g, s,
                                 cfg_big);
+        if (mid_tiles >= 256)
+            return launch_tiles(gemm_bf16_pipelined<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s,
+                                cfg_mid);
         return launch_tiles(gemm_bf16_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
                             cfg_small);
     }

@@ -105,6 +105,27 @@ def test_large_tile_path_with_ragged_edges():
     check_gemm_bf16(host_bits(y16), ref, oracle.row_norms(a[rows]), oracle.row_norms(b))
 
 
+def test_mid_tile_path_with_ragged_edges():
+    """A problem of one to two rounds of 256x256 tiles selects the 256x128 configuration."""
+    rng = np.random.default_rng(15)
+    M, N, K = 2100, 4000, 192
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    a = oracle.dequantize(ac, asc, 0.5)
+    b = oracle.dequantize(bc, bsc, 0.25)
+    rows = np.unique(np.concatenate([np.arange(0, M, 97), np.arange(M - 60, M), [255, 256, 257]]))
+    ref = oracle.gemm_f64(a[rows], b)
+    na, nb = oracle.row_norms(a[rows]), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    check_gemm_fp32(_gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32)[ridx].cpu().numpy(), ref, na, nb)
+    check_gemm_bf16(host_bits(_gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16)[ridx]), ref, na, nb)
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    w = wl.f32_to_bf16_bits(rng.standard_normal((N, K)).astype(np.float32))
+    a, b = oracle.bf16_to_f64(x[rows]), oracle.bf16_to_f64(w)
+    y = mq.bf16_gemm(dev_bf16(x), dev_bf16(w), mq.MQ_OUT_BF16)
+    check_gemm_bf16(host_bits(y[ridx]), oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b))
+
+
 def test_extreme_scales_subnormal_and_saturated():
     rng = np.random.default_rng(6)
     M, N, K = 70, 96, 256
