@@ -239,7 +239,7 @@ def main() -> int:
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}
                          for i, L in enumerate(layers)},
         "roofline": {
-            "kernel": "nvfp4 gemm (gemm_fp4_pipelined<256x256x64, 8 waves>)",
+            "kernel": "nvfp4 gemm (gemm_fp4_direct: 256x256 tile, 4 waves of 128x128, persistent)",
             "bound": "mfma",
             "achieved": round(gemm_tflops, 2),
             "peak": PEAK_MFMA_16BIT,

@@ -7,16 +7,25 @@
 // applies one power-of-two (E8M0) scale per 32 elements, and FP8 operands hold only 4
 // significant bits, so neither can carry sigma*q exactly.  sigma*q needs 6 significant bits
 // and lies in [2^-10, 2688]: it is exactly representable as a normal FP16 number.  The kernel
-// therefore expands each operand tile to FP16 once per workgroup while staging it into LDS
-// (v_cvt_scalef32_pk_f16_fp4 gives q*2^8, one packed FP16 multiply by sigma*2^-8 gives
-// sigma*q, both exact) and runs v_mfma_f32_32x32x16_f16 on it: every product is exact and the
-// only rounding is the FP32 accumulation.  alpha_a*alpha_b is applied once in the epilogue.
+// therefore expands the codes to FP16 (v_cvt_scalef32_pk_f16_fp4 gives q*2^8, one packed FP16
+// multiply by sigma*2^-8 gives sigma*q, both exact) and runs v_mfma_f32_32x32x16_f16 on them:
+// every product is exact and the only rounding is the FP32 accumulation.  alpha_a*alpha_b is
+// applied once in the epilogue.
 //
-// Structure shared by both products: block tile BM x BN x 64 (256x256 with 8 waves of 128x64, two
-// per SIMD; 128x128 with 4 waves of 64x64 for small problems), two LDS stages, and the latencies
-// covered inside each wave:
+// Kernels in this file
+//   gemm_fp4_direct     large NVFP4 problems.  256x256 tile, four waves of 128x128, persistent
+//                       workgroups; no LDS and no barriers: each wave loads its own operand rows
+//                       in MFMA order and expands them in registers (described at the kernel).
+//   gemm_fp4_pipelined  smaller NVFP4 problems (256x128 and 128x128 tiles): operands are expanded
+//                       once per workgroup while being staged into LDS.
+//   gemm_bf16_pipelined the BF16 baseline, same LDS pipeline.
+//   bf16_skinny_kernel  BF16 with M <= 64 (decode shapes), weight streaming.
+//   gemm_simple_kernel  any K % 16 == 0 / K % 8 == 0 that the tiled kernels do not take.
+//
+// The LDS pipeline (both *_pipelined kernels): block tile BM x BN x 64, two LDS stages, and the
+// latencies covered inside each wave:
 //   * a K step of 64 is four MFMA phases of 16; the fragments of phase p+1 are read from LDS
-//     into a second register set while the 16 MFMAs of phase p run;
+//     into a second register set while the MFMAs of phase p run;
 //   * NVFP4: the packed codes of a tile are fetched from global memory three K steps ahead into
 //     one of three register sets, and expanded to FP16 and written to the free LDS stage one
 //     quarter per phase, between the MFMAs; BF16: tiles are fetched one K step ahead into
@@ -101,25 +110,39 @@ __device__ __forceinline__ void sched_phase()
 }
 
 // Accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
+// A wave tile that lies wholly inside the output takes the first path: one uniform row pointer
+// per output row (scalar arithmetic) plus a constant 32-bit lane offset, no guards.  Tiles that
+// cross the M or N edge take the guarded element-by-element path.
 template <class C, bool OUT_BF16>
 __device__ __forceinline__ void epilogue(const GemmArgs &g, f32x16 (&acc)[C::TM][C::TN], float scale,
                                          int64_t m0, int64_t n0, int wm0, int wn0, int frow, int fhalf)
 {
+    using T = std::conditional_t<OUT_BF16, __bf16, float>;
+    const int64_t mw = m0 + wm0, nw = n0 + wn0;  // uniform over the wave
+    if (mw + C::WM <= g.M && nw + C::WN <= g.N && g.ldy * (int64_t)(4 * sizeof(T)) < (1ll << 31)) {
+        char *const base = static_cast<char *>(g.y) + (mw * g.ldy + nw) * (int64_t)sizeof(T);
+        const uint32_t lane_off = (uint32_t)((4 * fhalf) * g.ldy + frow) * (uint32_t)sizeof(T);
+        const int64_t row_bytes = g.ldy * (int64_t)sizeof(T);
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                char *const rowp = base + (int64_t)(i * 32 + 8 * (r / 4) + (r % 4)) * row_bytes;
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j)
+                    *reinterpret_cast<T *>(rowp + (uint64_t)lane_off + j * 32 * sizeof(T)) = (T)(acc[i][j][r] * scale);
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < C::TM; ++i)
 #pragma unroll
         for (int j = 0; j < C::TN; ++j) {
-            const int64_t n = n0 + wn0 + j * 32 + frow;
+            const int64_t n = nw + j * 32 + frow;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + wm0 + i * 32 + 8 * (r / 4) + 4 * fhalf + (r % 4);
-                if (m < g.M && n < g.N) {
-                    const float v = acc[i][j][r] * scale;
-                    if constexpr (OUT_BF16)
-                        static_cast<__bf16 *>(g.y)[m * g.ldy + n] = (__bf16)v;
-                    else
-                        static_cast<float *>(g.y)[m * g.ldy + n] = v;
-                }
+                const int64_t m = mw + i * 32 + 8 * (r / 4) + 4 * fhalf + (r % 4);
+                if (m < g.M && n < g.N) static_cast<T *>(g.y)[m * g.ldy + n] = (T)(acc[i][j][r] * scale);
             }
         }
 }
@@ -309,6 +332,171 @@ __global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int
 
     const float scale = (*g.a_alpha) * (*g.b_alpha);
     epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
+}
+
+// ---- NVFP4, register-direct ------------------------------------------------------------------
+
+// The same product without LDS and without barriers.  A wave owns a 128x128 output tile (four
+// waves, one per SIMD, cover 256x256) and loads the packed codes of its own 128 A rows and 128 B
+// rows straight from global memory in MFMA operand order: lane (r = lane%32, h = lane/32) takes
+// the 16 bytes h of row r's 32-byte K step, dword p of which feeds phase p.  Within a K step the
+// K index a lane supplies to the MFMA is therefore 32h + 8p + j instead of 16p + 8h + j; A and B
+// use the same map, so each MFMA still sums 16 matching products and a K step covers all 64.
+// Codes are expanded to FP16 in registers, one phase ahead of the MFMAs that use them; every
+// operand row is expanded by the two waves that share it (twice the conversion work of the LDS
+// pipeline, but no LDS traffic at all: measured 6 % faster on the 8192-token shapes).  Global
+// loads run two K steps ahead, and the first loads of a workgroup's next tile are issued before
+// the stores of the finished one.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+struct RawTile {
+    uint4 c[8];      // 4 A tiles, 4 B tiles: this lane's 32 codes of each
+    uint32_t s[8];   // the rows' four E4M3 scale bytes
+};
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, int tiles_n)
+{
+    using C = PCfg<256, 256, 2, 2>;
+    constexpr int NSETS = 2;  // register sets of prefetched codes (3 measured no faster)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / C::WAVES_N) * C::WM, wn0 = (wave % C::WAVES_N) * C::WN;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int KT = (int)(g.K / BK);
+    const int total_tiles = tiles_m * tiles_n;
+
+    // Buffer loads: a uniform resource per array, the K step in the scalar offset, the lane's
+    // row and half in a 32-bit vector offset.  No per-step address arithmetic in vector registers.
+    const uint32_t a_cb = (uint32_t)(g.M * (g.K / 2)), b_cb = (uint32_t)(g.N * (g.K / 2));
+    const __amdgpu_buffer_rsrc_t rac = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(g.a), 0, (int)a_cb, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rbc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(g.b), 0, (int)b_cb, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ras = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(g.a_scales), 0, (int)(a_cb / 8), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(g.b_scales), 0, (int)(b_cb / 8), 0x00020000);
+
+    uint32_t vc[8], vs[8];
+    auto set_tile = [&](int64_t m0, int64_t n0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bool isA = q < 4;
+            const int64_t total = isA ? g.M : g.N;
+            int64_t grow = (isA ? m0 + wm0 : n0 + wn0) + (q & 3) * 32 + frow;
+            grow = grow < total ? grow : total - 1;
+            vc[q] = (uint32_t)(grow * (isA ? g.a_c_row : g.b_c_row) + fhalf * 16);
+            vs[q] = (uint32_t)(grow * (isA ? g.a_s_row : g.b_s_row));
+        }
+    };
+    RawTile st[NSETS];
+    auto load_tile = [&](int t, RawTile &r) {
+        t = t < KT ? t : KT - 1;
+        const int oac = t * (int)g.a_c_step, obc = t * (int)g.b_c_step;
+        const int oas = t * (int)g.a_s_step, obs = t * (int)g.b_s_step;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < 4 ? rac : rbc, (int)vc[q], q < 4 ? oac : obc, 0);
+            r.c[q] = make_uint4(c[0], c[1], c[2], c[3]);
+            r.s[q] = __builtin_amdgcn_raw_buffer_load_b32(q < 4 ? ras : rbs, (int)vs[q], q < 4 ? oas : obs, 0);
+        }
+    };
+    // Scale register of the K step being expanded: sigma*2^-8 as FP16 for block 2h in the low
+    // half and for block 2h+1 in the high half (an E4M3 byte shifted left by 7 is that number).
+    // One byte permute picks the lane's two scale bytes, or zeros for a K step past the end.
+    uint32_t sg[8];
+    const uint32_t sel_valid = 0x0C000C00u | (uint32_t)(2 * fhalf) | ((uint32_t)(2 * fhalf + 1) << 16);
+    auto prep_scales = [&](const RawTile &r, bool valid) {
+        const uint32_t sel = valid ? sel_valid : 0x0C0C0C0Cu;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            uint32_t sc = r.s[q];
+            asm volatile("" : "+v"(sc));  // first use of the prefetched register stays here
+            sg[q] = __builtin_amdgcn_perm(0u, sc, sel) << 7;
+        }
+    };
+    uint4 fr[2][8];
+    auto expand_phase = [&](const RawTile &r, int p, uint4(&f)[8]) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            uint32_t w = p == 0 ? r.c[q].x : p == 1 ? r.c[q].y : p == 2 ? r.c[q].z : r.c[q].w;
+            asm volatile("" : "+v"(w));
+            const _Float16 sig = __builtin_bit_cast(_Float16, (uint16_t)(p < 2 ? sg[q] : sg[q] >> 16));
+            const f16x2 s = {sig, sig};
+            // four conversions, then four multiplies: a multiply issued right behind the
+            // conversion it consumes stalls the wave (measured 36 instead of 33 cycles per MFMA)
+            f16x2 c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 0);
+            f16x2 c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 1);
+            f16x2 c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 2);
+            f16x2 c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 3);
+            asm volatile("" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
+            c0 *= s, c1 *= s, c2 *= s, c3 *= s;
+            f[q] = make_uint4(__builtin_bit_cast(uint32_t, c0), __builtin_bit_cast(uint32_t, c1),
+                              __builtin_bit_cast(uint32_t, c2), __builtin_bit_cast(uint32_t, c3));
+        }
+    };
+    f32x16 acc[4][4];
+    auto mfmas = [&](const uint4(&f)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    __builtin_bit_cast(f16x8, f[i]), __builtin_bit_cast(f16x8, f[4 + j]), acc[i][j], 0, 0, 0);
+    };
+    // one K step; R = kt % NSETS is the register set that holds tile kt
+    auto kstep = [&](int kt, auto rr) {
+        constexpr int R = decltype(rr)::value;
+        RawTile &cur = st[R], &nxt = st[(R + 1) % NSETS];
+        expand_phase(cur, 1, fr[1]);
+        mfmas(fr[0]);
+        sched_phase<16, 0, 4, 0, 0>();
+        expand_phase(cur, 2, fr[0]);
+        mfmas(fr[1]);
+        sched_phase<16, 0, 4, 0, 0>();
+        expand_phase(cur, 3, fr[1]);
+        mfmas(fr[0]);
+        sched_phase<16, 0, 4, 0, 0>();
+        prep_scales(nxt, kt + 1 < KT);
+        expand_phase(nxt, 0, fr[0]);
+        load_tile(kt + NSETS, cur);
+        mfmas(fr[1]);
+        sched_phase<16, 0, 6, 0, 16>();
+    };
+
+    // Persistent workgroups: tile ids blockIdx.x, blockIdx.x + gridDim.x, ...  The first loads of
+    // the next tile are issued before the stores of the finished one.
+    const float scale = (*g.a_alpha) * (*g.b_alpha);
+    int tile = blockIdx.x;
+    int tm, tn;
+    tile_of(tile, tiles_m, tiles_n, tm, tn);
+    set_tile((int64_t)tm * C::BM, (int64_t)tn * C::BN);
+#pragma unroll
+    for (int u = 0; u < NSETS; ++u) load_tile(u, st[u]);
+    while (true) {
+        const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        prep_scales(st[0], true);
+        expand_phase(st[0], 0, fr[0]);
+        // No separate tail: the loop runs whole groups of NSETS K steps, and a step past the end
+        // multiplies by zero scales.  (Peeled tail steps make the compiler shuffle all 256
+        // accumulator registers at the control-flow joins.)
+        for (int kt = 0; kt < KT; kt += NSETS) {
+            kstep(kt, std::integral_constant<int, 0>{});
+            if constexpr (NSETS > 1) kstep(kt + 1, std::integral_constant<int, 1>{});
+            if constexpr (NSETS > 2) kstep(kt + 2, std::integral_constant<int, 2>{});
+        }
+        tile += gridDim.x;
+        const bool more = tile < total_tiles;
+        if (more) {
+            tile_of(tile, tiles_m, tiles_n, tm, tn);
+            set_tile((int64_t)tm * C::BM, (int64_t)tn * C::BN);
+#pragma unroll
+            for (int u = 0; u < NSETS; ++u) load_tile(u, st[u]);
+        }
+        epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
+        if (!more) break;
+    }
 }
 
 // ---- BF16 -----------------------------------------------------------------------------------
@@ -628,6 +816,29 @@ int launch_tiles(Kern kern, size_t lds_bytes, int bm, int bn, int threads, const
     return note_launch(hipGetLastError());
 }
 
+// Persistent 256x256 kernels: one workgroup per compute unit (a wave of 512 registers fills
+// its SIMD), each walking tile ids wg, wg + grid, ...
+template <class Kern>
+int launch_persistent(Kern kern, const GemmArgs &g, hipStream_t s)
+{
+    static std::atomic<int> cus{0};
+    int n = cus.load(std::memory_order_acquire);
+    if (n == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return note_launch(e);
+        n = n > 0 ? n / NUM_XCD * NUM_XCD : NUM_XCD;  // a multiple of the XCD count keeps wg % 8 = XCD
+        if (n == 0) n = NUM_XCD;
+        cus.store(n, std::memory_order_release);
+    }
+    const int64_t tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
+    if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    const int64_t grid = tiles_m * tiles_n < n ? tiles_m * tiles_n : n;
+    kern<<<dim3((unsigned)grid), dim3(256), 0, s>>>(g, (int)tiles_m, (int)tiles_n);
+    return note_launch(hipGetLastError());
+}
+
 template <bool FP4, bool OUT_BF16>
 int launch_simple(const GemmArgs &g, hipStream_t s)
 {
@@ -658,18 +869,15 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     }
     // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
-    // Large tiles once they fill the 256 CUs at least twice; smaller tiles below that.
+    // 256x256 tiles once they fill the 256 CUs at least twice; smaller tiles below that.
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    // 256x256: 8 waves of 128x64, two per SIMD (measured 3-4 % faster than 4 waves of 128x128:
-    // the second wave fills the issue slots the first leaves at barriers and waits)
-    using Big = PCfg<256, 256, 2, 4>;
+    using Big = PCfg<256, 256, 2, 4>;   // BF16 only: 8 waves of 128x64, two per SIMD
     using Mid = PCfg<256, 128, 2, 2>;   // 4 waves of 128x64: for problems of one to two rounds of 256x256 tiles
     using Small = PCfg<128, 128, 2, 2>;
     static std::atomic<bool> cfg_big{false}, cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
-        if (big_tiles >= 512)
-            return launch_tiles(gemm_fp4_pipelined<Big, OUT_BF16>, Big::LDS_BYTES, 256, 256, Big::THREADS, g, s, cfg_big);
+        if (big_tiles >= 512) return launch_persistent(gemm_fp4_direct<OUT_BF16>, g, s);
         if (mid_tiles >= 256)
             return launch_tiles(gemm_fp4_pipelined<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s, cfg_mid);
         return launch_tiles(gemm_fp4_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,

@@ -89,20 +89,45 @@ def test_ragged_shapes(M, N, K):
     _check_both(ac, asc, 0.013, bc, bsc, 0.0021)
 
 
-def test_large_tile_path_with_ragged_edges():
-    """Enough tiles to select the 256x256 configuration, with M and N off the tile grid."""
-    rng = np.random.default_rng(5)
-    M, N, K = 256 * 23 + 77, 256 * 23 + 40, 128
+@pytest.mark.parametrize("K", [128, 192, 320])
+def test_large_tile_path_with_ragged_edges(K):
+    """Enough tiles to select the 256x256 register-direct kernel (persistent workgroups, several
+    tiles each), with M and N off the tile grid; an odd number of K steps makes its K loop run
+    one step past the end with zeroed scales.  Both layouts, both output types."""
+    rng = np.random.default_rng(5 + K)
+    M, N = 256 * 23 + 77, 256 * 23 + 40
     ac, asc = _rand_nvfp4(rng, M, K)
     bc, bsc = _rand_nvfp4(rng, N, K)
     a = oracle.dequantize(ac, asc, 0.5)
     b = oracle.dequantize(bc, bsc, 0.25)
-    rows = np.unique(np.concatenate([np.arange(0, M, 251), np.arange(M - 80, M), [255, 256, 257]]))
+    rows = np.unique(np.concatenate([np.arange(0, M, 251), np.arange(M - 80, M), [127, 128, 255, 256, 257]]))
     ref = oracle.gemm_f64(a[rows], b)
-    y32 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32)[torch.from_numpy(rows).cuda()].cpu().numpy()
-    check_gemm_fp32(y32, ref, oracle.row_norms(a[rows]), oracle.row_norms(b))
-    y16 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16)[torch.from_numpy(rows).cuda()]
-    check_gemm_bf16(host_bits(y16), ref, oracle.row_norms(a[rows]), oracle.row_norms(b))
+    na, nb = oracle.row_norms(a[rows]), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        y32 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32, layout)
+        check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+        y16 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16, layout)
+        check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
+        # the two output types come from the same accumulators
+        assert torch.equal(y32.to(torch.bfloat16), y16)
+
+
+def test_large_tile_k_positions_one_hot():
+    """Register-direct kernel: an element at every k of a K step must meet exactly its partner.
+    A is a tall stack of one-hot rows (row r has a 1.0 at k = r % K), so Y[r, n] = B_hat[n, r % K]."""
+    K = 128
+    M, N = 256 * 22, 256 * 24
+    ac = np.zeros((M, K // 2), dtype=np.uint8)
+    asc = np.full((M, K // 16), 0x38, dtype=np.uint8)
+    k = np.arange(M) % K
+    ac[np.arange(M), k // 2] = (0x2 << (4 * (k & 1))).astype(np.uint8)
+    rng = np.random.default_rng(18)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    b = oracle.dequantize(bc, bsc, 1.0)
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        y = _gpu_gemm(ac, asc, 1.0, bc, bsc, 1.0, mq.MQ_OUT_FP32, layout).cpu().numpy().astype(np.float64)
+        assert np.array_equal(y, b.T[k])
 
 
 def test_mid_tile_path_with_ragged_edges():
