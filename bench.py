@@ -222,8 +222,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "nvfp4 (e2m1 x e4m3 block scales) expanded exactly to fp16 MFMA, fp32 accumulate, bf16 out",
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: Llama-3-8B-shaped prefill linears (qkv, o, gate_up, down) at M={M}, "
-                               "NVFP4 W4A4, quantize+GEMM per layer", "M": M,
+        "config": {"workload": f"{cfg.name}: prefill linear layers ({', '.join(L['layer'].name for L in layers)}) "
+                               f"at M={M} tokens, NVFP4 W4A4, quantize+GEMM per layer", "M": M,
                    "layers": [[L["layer"].name, L["layer"].K, L["layer"].N] for L in layers]},
         "pct_of_fp4_mfma_peak": round(100.0 * tflops / PEAK_MFMA_FP4, 2),
         "pct_of_16bit_mfma_peak": round(100.0 * tflops / PEAK_MFMA_16BIT, 2),

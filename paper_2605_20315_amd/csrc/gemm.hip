@@ -13,11 +13,13 @@
 // applied once in the epilogue.
 //
 // Kernels in this file
-//   gemm_fp4_direct     large NVFP4 problems.  256x256 tile, four waves of 128x128, persistent
-//                       workgroups; no LDS and no barriers: each wave loads its own operand rows
-//                       in MFMA order and expands them in registers (described at the kernel).
-//   gemm_fp4_pipelined  smaller NVFP4 problems (256x128 and 128x128 tiles): operands are expanded
-//                       once per workgroup while being staged into LDS.
+//   gemm_fp4_direct     NVFP4 problems that fill at least half of the chip.  Four waves of
+//                       128x128 per workgroup, persistent workgroups, no LDS and no barriers in
+//                       the K loop: each wave loads its own operand rows in MFMA order and
+//                       expands them in registers (described at the kernel).  Either a 256x256
+//                       tile, or a 256x128 tile with K split over wave pairs.
+//   gemm_fp4_pipelined  small NVFP4 problems (128x128 tiles): operands are expanded once per
+//                       workgroup while being staged into LDS.
 //   gemm_bf16_pipelined the BF16 baseline, same LDS pipeline.
 //   bf16_skinny_kernel  BF16 with M <= 64 (decode shapes), weight streaming.
 //   gemm_simple_kernel  any K % 16 == 0 / K % 8 == 0 that the tiled kernels do not take.
@@ -113,18 +115,19 @@ __device__ __forceinline__ void sched_phase()
 // A wave tile that lies wholly inside the output takes the first path: one uniform row pointer
 // per output row (scalar arithmetic) plus a constant 32-bit lane offset, no guards.  Tiles that
 // cross the M or N edge take the guarded element-by-element path.
-template <class C, bool OUT_BF16>
+// I0, NI: the wave stores only its 32-row tiles I0 .. I0+NI-1.
+template <class C, bool OUT_BF16, int I0 = 0, int NI = C::TM>
 __device__ __forceinline__ void epilogue(const GemmArgs &g, f32x16 (&acc)[C::TM][C::TN], float scale,
                                          int64_t m0, int64_t n0, int wm0, int wn0, int frow, int fhalf)
 {
     using T = std::conditional_t<OUT_BF16, __bf16, float>;
     const int64_t mw = m0 + wm0, nw = n0 + wn0;  // uniform over the wave
-    if (mw + C::WM <= g.M && nw + C::WN <= g.N && g.ldy * (int64_t)(4 * sizeof(T)) < (1ll << 31)) {
+    if (mw + (I0 + NI) * 32 <= g.M && nw + C::WN <= g.N && g.ldy * (int64_t)(4 * sizeof(T)) < (1ll << 31)) {
         char *const base = static_cast<char *>(g.y) + (mw * g.ldy + nw) * (int64_t)sizeof(T);
         const uint32_t lane_off = (uint32_t)((4 * fhalf) * g.ldy + frow) * (uint32_t)sizeof(T);
         const int64_t row_bytes = g.ldy * (int64_t)sizeof(T);
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i)
+        for (int i = I0; i < I0 + NI; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 char *const rowp = base + (int64_t)(i * 32 + 8 * (r / 4) + (r % 4)) * row_bytes;
@@ -135,7 +138,7 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, f32x16 (&acc)[C::TM]
         return;
     }
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i)
+    for (int i = I0; i < I0 + NI; ++i)
 #pragma unroll
         for (int j = 0; j < C::TN; ++j) {
             const int64_t n = nw + j * 32 + frow;
@@ -353,15 +356,27 @@ struct RawTile {
     uint32_t s[8];   // the rows' four E4M3 scale bytes
 };
 
-template <bool OUT_BF16>
+// SPLIT = 2 (problems that fill the chip only with finer tiles): the workgroup tile is 256x128,
+// its four waves are two 128x128 wave tiles times two halves of K; after the K loop each wave
+// hands the half of its accumulators that its partner will store to the partner through LDS.
+template <bool OUT_BF16, int SPLIT>
 __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, int tiles_n)
 {
-    using C = PCfg<256, 256, 2, 2>;
+    using C = PCfg<256, 256, 2, 2>;  // wave-level constants: 128x128 wave tile, 4x4 MFMA tiles
+    constexpr int BM = 256, BN = SPLIT == 1 ? 256 : 128;
     constexpr int NSETS = 2;  // register sets of prefetched codes (3 measured no faster)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / C::WAVES_N) * C::WM, wn0 = (wave % C::WAVES_N) * C::WN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the K range depends on it
+    const int wm0 = SPLIT == 1 ? (wave >> 1) * 128 : (wave & 1) * 128, wn0 = SPLIT == 1 ? (wave & 1) * 128 : 0;
+    const int khalf = SPLIT == 1 ? 0 : wave >> 1;
+    // SPLIT = 2: the wave of the second K half holds its 32-row A tiles in the order 2,3,0,1, so
+    // that both waves of a pair keep accumulator rows 0..1 and send rows 2..3 (no divergent code)
+    const int aswap = khalf << 1;
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = (int)(g.K / BK);
+    // this wave's K steps [k0, k1); the first half is a whole number of NSETS groups
+    const int KH = SPLIT == 1 ? KT : ((KT + 1) / 2 + NSETS - 1) / NSETS * NSETS;
+    const int k0 = khalf * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
     const int total_tiles = tiles_m * tiles_n;
 
     // Buffer loads: a uniform resource per array, the K step in the scalar offset, the lane's
@@ -378,7 +393,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         for (int q = 0; q < 8; ++q) {
             const bool isA = q < 4;
             const int64_t total = isA ? g.M : g.N;
-            int64_t grow = (isA ? m0 + wm0 : n0 + wn0) + (q & 3) * 32 + frow;
+            int64_t grow = (isA ? m0 + wm0 + ((q & 3) ^ aswap) * 32 : n0 + wn0 + (q & 3) * 32) + frow;
             grow = grow < total ? grow : total - 1;
             vc[q] = (uint32_t)(grow * (isA ? g.a_c_row : g.b_c_row) + fhalf * 16);
             vs[q] = (uint32_t)(grow * (isA ? g.a_s_row : g.b_s_row));
@@ -452,7 +467,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         expand_phase(cur, 3, fr[1]);
         mfmas(fr[0]);
         sched_phase<16, 0, 4, 0, 0>();
-        prep_scales(nxt, kt + 1 < KT);
+        prep_scales(nxt, kt + 1 < k1);
         expand_phase(nxt, 0, fr[0]);
         load_tile(kt + NSETS, cur);
         mfmas(fr[1]);
@@ -465,23 +480,23 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     int tile = blockIdx.x;
     int tm, tn;
     tile_of(tile, tiles_m, tiles_n, tm, tn);
-    set_tile((int64_t)tm * C::BM, (int64_t)tn * C::BN);
+    set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
-    for (int u = 0; u < NSETS; ++u) load_tile(u, st[u]);
+    for (int u = 0; u < NSETS; ++u) load_tile(k0 + u, st[u]);
     while (true) {
-        const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
+        const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-        prep_scales(st[0], true);
+        prep_scales(st[0], k0 < k1);
         expand_phase(st[0], 0, fr[0]);
         // No separate tail: the loop runs whole groups of NSETS K steps, and a step past the end
         // multiplies by zero scales.  (Peeled tail steps make the compiler shuffle all 256
         // accumulator registers at the control-flow joins.)
-        for (int kt = 0; kt < KT; kt += NSETS) {
+        for (int kt = k0; kt < k1; kt += NSETS) {
             kstep(kt, std::integral_constant<int, 0>{});
             if constexpr (NSETS > 1) kstep(kt + 1, std::integral_constant<int, 1>{});
             if constexpr (NSETS > 2) kstep(kt + 2, std::integral_constant<int, 2>{});
@@ -490,11 +505,46 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         const bool more = tile < total_tiles;
         if (more) {
             tile_of(tile, tiles_m, tiles_n, tm, tn);
-            set_tile((int64_t)tm * C::BM, (int64_t)tn * C::BN);
+            set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
-            for (int u = 0; u < NSETS; ++u) load_tile(u, st[u]);
+            for (int u = 0; u < NSETS; ++u) load_tile(k0 + u, st[u]);
         }
-        epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
+        if constexpr (SPLIT == 1) {
+            epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
+        } else {
+            // Waves w and w^2 hold the two K halves of the same 128x128 tile.  Each keeps its
+            // accumulator rows 0..1 (output rows 0..63 in the first-half wave, 64..127 in the
+            // other, see aswap), sends rows 2..3 to its partner through LDS and adds what it
+            // receives (a + b in both, so the result does not depend on which wave adds).
+            // 1 KB per (32x32 tile, register quad) and wave.
+            extern __shared__ uint4 lds[];
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            f32x4 *const X = reinterpret_cast<f32x4 *>(lds);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const f32x16 &t = acc[2 + i][j];
+                        X[((wave * 8 + i * 4 + j) * 4 + c) * 64 + lane] =
+                            f32x4{t[4 * c], t[4 * c + 1], t[4 * c + 2], t[4 * c + 3]};
+                    }
+            __syncthreads();
+            const int partner = wave ^ 2;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const f32x4 v = X[((partner * 8 + i * 4 + j) * 4 + c) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * c + e] += v[e];
+                    }
+            __syncthreads();  // the next tile's sends must not overtake these reads
+            epilogue<C, OUT_BF16, 0, 2>(g, acc, scale, m0, n0, wm0 + khalf * 64, wn0, frow, fhalf);
+        }
         if (!more) break;
     }
 }
@@ -816,26 +866,37 @@ int launch_tiles(Kern kern, size_t lds_bytes, int bm, int bn, int threads, const
     return note_launch(hipGetLastError());
 }
 
-// Persistent 256x256 kernels: one workgroup per compute unit (a wave of 512 registers fills
-// its SIMD), each walking tile ids wg, wg + grid, ...
-template <class Kern>
-int launch_persistent(Kern kern, const GemmArgs &g, hipStream_t s)
+// Persistent register-direct kernels: one workgroup per compute unit (a wave of 512 registers
+// fills its SIMD), each walking tile ids wg, wg + grid, ...
+inline int compute_units(int &n)
 {
     static std::atomic<int> cus{0};
-    int n = cus.load(std::memory_order_acquire);
+    n = cus.load(std::memory_order_acquire);
     if (n == 0) {
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         if (e != hipSuccess) return note_launch(e);
-        n = n > 0 ? n / NUM_XCD * NUM_XCD : NUM_XCD;  // a multiple of the XCD count keeps wg % 8 = XCD
-        if (n == 0) n = NUM_XCD;
+        n = n >= NUM_XCD ? n / NUM_XCD * NUM_XCD : NUM_XCD;  // a multiple of the XCD count keeps wg % 8 = XCD
         cus.store(n, std::memory_order_release);
     }
-    const int64_t tiles_m = (g.M + 255) / 256, tiles_n = (g.N + 255) / 256;
+    return MQ_OK;
+}
+
+template <class Kern>
+int launch_persistent(Kern kern, int bn, size_t lds_bytes, const GemmArgs &g, hipStream_t s, int cus,
+                      std::atomic<bool> &configured)
+{
+    if (lds_bytes > 0 && !configured.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return note_launch(e);
+        configured.store(true, std::memory_order_release);
+    }
+    const int64_t tiles_m = (g.M + 255) / 256, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
-    const int64_t grid = tiles_m * tiles_n < n ? tiles_m * tiles_n : n;
-    kern<<<dim3((unsigned)grid), dim3(256), 0, s>>>(g, (int)tiles_m, (int)tiles_n);
+    const int64_t grid = tiles_m * tiles_n < cus ? tiles_m * tiles_n : cus;
+    kern<<<dim3((unsigned)grid), dim3(256), lds_bytes, s>>>(g, (int)tiles_m, (int)tiles_n);
     return note_launch(hipGetLastError());
 }
 
@@ -869,20 +930,29 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     }
     // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
-    // 256x256 tiles once they fill the 256 CUs at least twice; smaller tiles below that.
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
     using Big = PCfg<256, 256, 2, 4>;   // BF16 only: 8 waves of 128x64, two per SIMD
-    using Mid = PCfg<256, 128, 2, 2>;   // 4 waves of 128x64: for problems of one to two rounds of 256x256 tiles
+    using Mid = PCfg<256, 128, 2, 2>;   // BF16 only: 4 waves of 128x64, for one to two rounds of 256x256 tiles
     using Small = PCfg<128, 128, 2, 2>;
     static std::atomic<bool> cfg_big{false}, cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
-        if (big_tiles >= 512) return launch_persistent(gemm_fp4_direct<OUT_BF16>, g, s);
-        if (mid_tiles >= 256)
-            return launch_tiles(gemm_fp4_pipelined<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s, cfg_mid);
+        // Register-direct kernel once 256x128 workgroups fill at least half of the chip: whole
+        // 256x256 tiles, or 256x128 tiles with K split over wave pairs when that wastes less of
+        // the last round (such a workgroup takes 0.55 of the time of a whole one, measured).
+        // Below that, 128x128 LDS-pipelined tiles.
+        int cus = 0;
+        if (int rc = compute_units(cus)) return rc;
+        const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus;
+        static std::atomic<bool> cfg_d1{false}, cfg_d2{false};
+        if (2 * mid_tiles >= cus && 100 * r1 > 55 * r2)
+            return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 128, 128 * 1024, g, s, cus, cfg_d2);
+        if (2 * mid_tiles >= cus)
+            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 0, g, s, cus, cfg_d1);
         return launch_tiles(gemm_fp4_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
                             cfg_small);
     } else {
+        // 256x256 tiles once they fill the 256 CUs at least twice; smaller tiles below that.
         if (big_tiles >= 512)
             return launch_tiles(gemm_bf16_pipelined<Big, OUT_BF16>, Big::LDS_BYTES, 256, 256, Big::THREADS, g, s,
                                 cfg_big);

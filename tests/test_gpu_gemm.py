@@ -91,11 +91,11 @@ def test_ragged_shapes(M, N, K):
 
 @pytest.mark.parametrize("K", [128, 192, 320])
 def test_large_tile_path_with_ragged_edges(K):
-    """Enough tiles to select the 256x256 register-direct kernel (persistent workgroups, several
-    tiles each), with M and N off the tile grid; an odd number of K steps makes its K loop run
-    one step past the end with zeroed scales.  Both layouts, both output types."""
+    """16 x 32 tiles of 256x256 select the register-direct kernel with whole tiles (persistent
+    workgroups, two tiles each), with M and N off the tile grid; an odd number of K steps makes
+    its K loop run one step past the end with zeroed scales.  Both layouts, both output types."""
     rng = np.random.default_rng(5 + K)
-    M, N = 256 * 23 + 77, 256 * 23 + 40
+    M, N = 256 * 15 + 77, 256 * 31 + 40
     ac, asc = _rand_nvfp4(rng, M, K)
     bc, bsc = _rand_nvfp4(rng, N, K)
     a = oracle.dequantize(ac, asc, 0.5)
@@ -113,11 +113,12 @@ def test_large_tile_path_with_ragged_edges(K):
         assert torch.equal(y32.to(torch.bfloat16), y16)
 
 
-def test_large_tile_k_positions_one_hot():
-    """Register-direct kernel: an element at every k of a K step must meet exactly its partner.
-    A is a tall stack of one-hot rows (row r has a 1.0 at k = r % K), so Y[r, n] = B_hat[n, r % K]."""
+@pytest.mark.parametrize("M,N", [(256 * 16, 256 * 32), (2048, 4096)])
+def test_register_direct_k_positions_one_hot(M, N):
+    """Register-direct kernel, whole tiles and split K: an element at every k of a K step must
+    meet exactly its partner.  A is a tall stack of one-hot rows (row r has a 1.0 at k = r % K),
+    so Y[r, n] = B_hat[n, r % K]."""
     K = 128
-    M, N = 256 * 22, 256 * 24
     ac = np.zeros((M, K // 2), dtype=np.uint8)
     asc = np.full((M, K // 16), 0x38, dtype=np.uint8)
     k = np.arange(M) % K
@@ -130,20 +131,27 @@ def test_large_tile_k_positions_one_hot():
         assert np.array_equal(y, b.T[k])
 
 
-def test_mid_tile_path_with_ragged_edges():
-    """A problem of one to two rounds of 256x256 tiles selects the 256x128 configuration."""
-    rng = np.random.default_rng(15)
-    M, N, K = 2100, 4000, 192
+@pytest.mark.parametrize("K", [64, 192, 448])
+def test_split_k_path_with_ragged_edges(K):
+    """256 workgroup tiles of 256x128 select the register-direct kernel with K split over wave
+    pairs (one K step: the second half is empty; three and seven: halves of unequal length, the
+    second ending on a zeroed extra step).  The BF16 baseline takes its 256x128 configuration."""
+    rng = np.random.default_rng(15 + K)
+    M, N = 2000, 4000
     ac, asc = _rand_nvfp4(rng, M, K)
     bc, bsc = _rand_nvfp4(rng, N, K)
     a = oracle.dequantize(ac, asc, 0.5)
     b = oracle.dequantize(bc, bsc, 0.25)
-    rows = np.unique(np.concatenate([np.arange(0, M, 97), np.arange(M - 60, M), [255, 256, 257]]))
+    rows = np.unique(np.concatenate([np.arange(0, M, 97), np.arange(M - 60, M), [63, 64, 127, 128, 255, 256, 257]]))
     ref = oracle.gemm_f64(a[rows], b)
     na, nb = oracle.row_norms(a[rows]), oracle.row_norms(b)
     ridx = torch.from_numpy(rows).cuda()
-    check_gemm_fp32(_gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32)[ridx].cpu().numpy(), ref, na, nb)
-    check_gemm_bf16(host_bits(_gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16)[ridx]), ref, na, nb)
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        y32 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32, layout)
+        check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+        y16 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16, layout)
+        check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
+        assert torch.equal(y32.to(torch.bfloat16), y16)
     x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
     w = wl.f32_to_bf16_bits(rng.standard_normal((N, K)).astype(np.float32))
     a, b = oracle.bf16_to_f64(x[rows]), oracle.bf16_to_f64(w)
