@@ -379,14 +379,10 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     const int k0 = khalf * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
     const int total_tiles = tiles_m * tiles_n;
 
-    // Buffer loads: a uniform resource per array, the K step in the scalar offset, the lane's
-    // row and half in a 32-bit vector offset.  No per-step address arithmetic in vector registers.
-    const uint32_t a_cb = (uint32_t)(g.M * (g.K / 2)), b_cb = (uint32_t)(g.N * (g.K / 2));
-    const __amdgpu_buffer_rsrc_t rac = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(g.a), 0, (int)a_cb, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rbc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(g.b), 0, (int)b_cb, 0x00020000);
-    const __amdgpu_buffer_rsrc_t ras = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(g.a_scales), 0, (int)(a_cb / 8), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rbs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(g.b_scales), 0, (int)(b_cb / 8), 0x00020000);
-
+    // Buffer loads: per K step a uniform resource whose 64-bit base is the start of that K step
+    // (scalar arithmetic only), plus the lane's row and half as a 32-bit vector offset.  Rows
+    // are clamped below, so every access is in bounds by construction and the resources carry
+    // the maximal size.
     uint32_t vc[8], vs[8];
     auto set_tile = [&](int64_t m0, int64_t n0) {
 #pragma unroll
@@ -402,13 +398,18 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     RawTile st[NSETS];
     auto load_tile = [&](int t, RawTile &r) {
         t = t < KT ? t : KT - 1;
-        const int oac = t * (int)g.a_c_step, obc = t * (int)g.b_c_step;
-        const int oas = t * (int)g.a_s_step, obs = t * (int)g.b_s_step;
+        auto rsrc = [](const void *base, int64_t off) {
+            return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(static_cast<const char *>(base)) + off, 0, -1,
+                                                     0x00020000);
+        };
+        const __amdgpu_buffer_rsrc_t rac = rsrc(g.a, (int64_t)t * g.a_c_step), rbc = rsrc(g.b, (int64_t)t * g.b_c_step);
+        const __amdgpu_buffer_rsrc_t ras = rsrc(g.a_scales, (int64_t)t * g.a_s_step);
+        const __amdgpu_buffer_rsrc_t rbs = rsrc(g.b_scales, (int64_t)t * g.b_s_step);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < 4 ? rac : rbc, (int)vc[q], q < 4 ? oac : obc, 0);
+            const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < 4 ? rac : rbc, (int)vc[q], 0, 0);
             r.c[q] = make_uint4(c[0], c[1], c[2], c[3]);
-            r.s[q] = __builtin_amdgcn_raw_buffer_load_b32(q < 4 ? ras : rbs, (int)vs[q], q < 4 ? oas : obs, 0);
+            r.s[q] = __builtin_amdgcn_raw_buffer_load_b32(q < 4 ? ras : rbs, (int)vs[q], 0, 0);
         }
     };
     // Scale register of the K step being expanded: sigma*2^-8 as FP16 for block 2h in the low

@@ -159,6 +159,34 @@ def test_split_k_path_with_ragged_edges(K):
     check_gemm_bf16(host_bits(y[ridx]), oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b))
 
 
+@pytest.mark.timeout(600)
+def test_operand_larger_than_2_gib():
+    """An activation operand of 2.3 GB: K-step and row offsets pass 2^31 in both layouts."""
+    M, N, K = 320000, 256, 14336
+    rng = np.random.default_rng(77)
+    ac = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    asc = rng.integers(0x30, 0x40, size=(M, K // 16), dtype=np.uint8)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    rows = np.unique(np.concatenate([rng.integers(0, M, 48), [0, 1, 299593, 299594, M - 257, M - 256, M - 2, M - 1]]))
+    a = oracle.dequantize(ac[rows], asc[rows], 0.5)
+    b = oracle.dequantize(bc, bsc, 0.25)
+    ref = oracle.gemm_f64(a, b)
+    na, nb = oracle.row_norms(a), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        print(f"\n[case] layout={layout}", flush=True)
+        A = (ac, asc) if layout == mq.MQ_LAYOUT_LINEAR else to_ktile(ac, asc)
+        B = (bc, bsc) if layout == mq.MQ_LAYOUT_LINEAR else to_ktile(bc, bsc)
+        acd, asd = dev_u8(A[0]), dev_u8(A[1])
+        del A
+        y = mq.nvfp4_gemm(acd, asd, dev_scalar(0.5), dev_u8(B[0]), dev_u8(B[1]), dev_scalar(0.25), mq.MQ_OUT_FP32,
+                          None, layout)
+        torch.cuda.synchronize()
+        check_gemm_fp32(y[ridx].cpu().numpy(), ref, na, nb)
+        del acd, asd, y
+        torch.cuda.empty_cache()
+
+
 def test_extreme_scales_subnormal_and_saturated():
     rng = np.random.default_rng(6)
     M, N, K = 70, 96, 256
