@@ -38,6 +38,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload config id (2 = Llama-3-8B shapes, M=8192)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the tokens-per-batch sweep (second workload)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -198,6 +199,49 @@ def main() -> int:
         torch.cuda.synchronize()
         decode[f"M={md}"] = round(20 * w_bytes / (g0.elapsed_time(g1) * 1e-3) * 1e-9, 1)
 
+    # ---- second workload: the paper's sweep axis (Section 4.4, Fig. 3: prefill speed-up over BF16
+    # against context length / batch), as tokens M per prefill batch on the same layer set.
+    # Activations are generated on the device (N(0,1), 0.1 % of the channels scaled by 20: the
+    # recipe of the headline workload without its host generator); weights are the headline's. ----
+    sweep = None
+    if args.config == 2 and not args.no_sweep:
+        sweep = {}
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1234)
+        for ms in (2048, 4096, 16384, 32768, 65536, 131072):
+            t_q4 = t_b16 = 0.0
+            for L in layers:
+                K, N = L["layer"].K, L["layer"].N
+                x = torch.randn((ms, K), dtype=torch.bfloat16, device="cuda", generator=gen)
+                cols = torch.randperm(K, device="cuda", generator=gen)[:max(1, round(0.001 * K))]
+                x[:, cols] *= 20.0
+                ax = mq.nvfp4_global_scale(x)
+                xc = torch.empty((ms, K // 2), dtype=torch.uint8, device="cuda")
+                xs = torch.empty((ms, K // 16), dtype=torch.uint8, device="cuda")
+                y = torch.empty((ms, N), dtype=torch.bfloat16, device="cuda")
+
+                def one():
+                    mq.nvfp4_quantize(x, ax, xc, xs, LAYOUT)
+                    mq.nvfp4_gemm(xc, xs, ax, L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, y, LAYOUT)
+                for fn, reps in ((one, 3), (lambda: mq.bf16_gemm(x, L["w"], mq.MQ_OUT_BF16, y), 2)):
+                    fn()
+                    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    s0.record()
+                    for _ in range(reps):
+                        fn()
+                    s1.record()
+                    torch.cuda.synchronize()
+                    if fn is one:
+                        t_q4 += s0.elapsed_time(s1) / reps
+                    else:
+                        t_b16 += s0.elapsed_time(s1) / reps
+                del x, xc, xs, y
+            fl = sum(wl.layer_flops(ms, L["layer"]) for L in layers)
+            sweep[f"M={ms}"] = {"nvfp4_quant_plus_gemm_tflops": round(fl / (t_q4 * 1e-3) * 1e-12, 1),
+                                "bf16_gemm_tflops": round(fl / (t_b16 * 1e-3) * 1e-12, 1),
+                                "x_vs_bf16_gemm": round(t_b16 / t_q4, 3)}
+            torch.cuda.empty_cache()
+
     # ---- what the matrix pipe sustains on this machine for random FP16 operands (measured roof) ----
     for _ in range(3):
         mq.mfma_probe(20000)
@@ -234,6 +278,7 @@ def main() -> int:
         "dynamic_alpha_pipeline_tflops": round(flop_step / (dyn_ms_step * 1e-3) * 1e-12, 2),
         "global_scale_gbs": round(amax_gbs, 1),
         "decode_bf16_gemm_weight_gbs": decode,
+        "tokens_per_batch_sweep": sweep,
         "quantizer_gbs": round(quant_gbs, 1),
         "quantizer_pct_of_hbm_peak": round(100.0 * quant_gbs / PEAK_HBM_GBS, 1),
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}
