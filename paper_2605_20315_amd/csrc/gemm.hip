@@ -675,95 +675,125 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
 // ---- decode-shape BF16 product (M <= 64): weight streaming, HBM-bound ---------------------------
 
 // The high-precision decode path multiplies a handful of tokens by the whole weight matrix, so
-// the time is the time to stream W once from HBM.  A workgroup of 8 waves owns 16 rows of W; wave
-// w takes the 128-wide K super-steps w, w+8, ... (together 2 KB contiguous per row and round), so
-// 8 x (N/16) waves keep enough bytes in flight without splitting K across workgroups.  A lane
-// (row r = lane%16, group g = lane/16) loads 64 contiguous bytes of W row r and of X rows
-// r, r+16, ...; four v_mfma_f32_16x16x32_bf16 per super-step and token group accumulate
-// D[W row][token]; the 8 partial sums are added in a fixed order through LDS.
-template <int MT, bool OUT_BF16>
+// the time is the time to stream W once from HBM.  A workgroup of 8 waves owns 16*RT rows of W;
+// wave w takes the 128-wide K super-steps w, w+8, ... (together 2 KB contiguous per row and round),
+// so 8 x (N / (16*RT)) waves keep enough bytes in flight without splitting K across workgroups.
+// A lane (row r = lane%16, group g = lane/16) loads 64 contiguous bytes of W rows r, r+16, ... and
+// of X rows r, r+16, ...; four v_mfma_f32_16x16x32_bf16 per super-step and (row tile, token tile)
+// pair accumulate D[W row][token]; the 8 partial sums are added pairwise, in a fixed order,
+// through LDS.  Every workgroup re-reads the activations from L2, which delivers about 6 TB/s to
+// the CUs in total: with MT token tiles and RT row tiles per wave the weights stream at
+// 6 / (1 + MT/RT) TB/s at best, so RT grows with N as far as the grid still covers half the chip.
+// DB: two super-steps of loads in flight per wave (when the registers allow), else one.
+template <int MT, int RT, bool DB, bool OUT_BF16>
 __global__ __launch_bounds__(512) void bf16_skinny_kernel(GemmArgs g)
 {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
-    __shared__ float red[8][MT][64][4];
+    constexpr int NT = RT * MT;
+    __shared__ f32x4 red[4][NT][64];  // 4 * NT KB: at most 64 KB
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = lane & 15, grp = lane >> 4;
-    const int64_t n0 = (int64_t)blockIdx.x * 16;
-    int64_t wr = n0 + row;
-    wr = wr < g.N ? wr : g.N - 1;
-    const uint4 *wp = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.b) + wr * g.ldb + grp * 32);
-    const uint4 *xp[MT];
+    const int64_t n0 = (int64_t)blockIdx.x * (16 * RT);
+    const uint4 *wp[RT], *xp[MT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+        int64_t wr = n0 + r * 16 + row;
+        wr = wr < g.N ? wr : g.N - 1;
+        wp[r] = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.b) + wr * g.ldb + grp * 32);
+    }
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
         int64_t xr = t * 16 + row;
         xr = xr < g.M ? xr : g.M - 1;
         xp[t] = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.a) + xr * g.lda + grp * 32);
     }
-    f32x4 acc[MT];
+    f32x4 acc[RT][MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) acc[r][t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int S = (int)(g.K / 128);  // super-steps; 16 uint4 per row each
-    auto step = [&](int s, const uint4(&w)[4], const uint4(&x)[MT][4]) {
-        (void)s;
+    auto load = [&](int s, uint4(&w)[RT][4], uint4(&x)[MT][4]) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[j]),
-                                                                 __builtin_bit_cast(bf16x8, x[t][j]), acc[t], 0, 0, 0);
-    };
-    auto load = [&](int s, uint4(&w)[4], uint4(&x)[MT][4]) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = wp[s * 16 + j];
+            for (int j = 0; j < 4; ++j) w[r][j] = wp[r][s * 16 + j];
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int j = 0; j < 4; ++j) x[t][j] = xp[t][s * 16 + j];
     };
+    auto step = [&](const uint4(&w)[RT][4], const uint4(&x)[MT][4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, w[r][j]), __builtin_bit_cast(bf16x8, x[t][j]), acc[r][t], 0, 0, 0);
+    };
     int s = wave;
-    for (; s + 8 < S; s += 16) {  // two super-steps of loads in flight
-        uint4 w0[4], w1[4], x0[MT][4], x1[MT][4];
-        load(s, w0, x0);
-        load(s + 8, w1, x1);
-        step(s, w0, x0);
-        step(s + 8, w1, x1);
-    }
-    if (s < S) {
-        uint4 w0[4], x0[MT][4];
-        load(s, w0, x0);
-        step(s, w0, x0);
-    }
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) red[wave][t][lane][i] = acc[t][i];
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            float v[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float sum = red[0][t][lane][i];
-#pragma unroll
-                for (int w = 1; w < 8; ++w) sum += red[w][t][lane][i];
-                v[i] = sum;
-            }
-            // accumulator i of a 16x16 tile: W row 4*(lane/16) + i, token lane%16
-            const int64_t m = t * 16 + row, n = n0 + 4 * grp;
-            if (m < g.M) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (n + i < g.N) {
-                        if constexpr (OUT_BF16)
-                            static_cast<__bf16 *>(g.y)[m * g.ldy + n + i] = (__bf16)v[i];
-                        else
-                            static_cast<float *>(g.y)[m * g.ldy + n + i] = v[i];
-                    }
-            }
+    if constexpr (DB) {
+        for (; s + 8 < S; s += 16) {  // two super-steps of loads in flight
+            uint4 w0[RT][4], w1[RT][4], x0[MT][4], x1[MT][4];
+            load(s, w0, x0);
+            load(s + 8, w1, x1);
+            __builtin_amdgcn_sched_barrier(0);  // every load is issued before the first MFMA waits
+            step(w0, x0);
+            step(w1, x1);
         }
     }
+    for (; s < S; s += 8) {
+        uint4 w0[RT][4], x0[MT][4];
+        load(s, w0, x0);
+        __builtin_amdgcn_sched_barrier(0);
+        step(w0, x0);
+    }
+
+    // waves 4..7 hand their sums to waves 0..3, then 2..3 to 0..1, then 1 to 0
+#pragma unroll
+    for (int h = 4; h >= 1; h >>= 1) {
+        if (wave >= h && wave < 2 * h) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) red[wave - h][r * MT + t][lane] = acc[r][t];
+        }
+        __syncthreads();
+        if (wave < h) {
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+                for (int t = 0; t < MT; ++t) acc[r][t] += red[wave][r * MT + t][lane];
+        }
+        __syncthreads();
+    }
+    if (wave != 0) return;
+    // accumulator i of a 16x16 tile: W row 4*(lane/16) + i, token lane%16
+    using T = std::conditional_t<OUT_BF16, __bf16, float>;
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int64_t m = t * 16 + row, n = n0 + r * 16 + 4 * grp;
+            if (m >= g.M) continue;
+            T *dst = static_cast<T *>(g.y) + m * g.ldy + n;
+            if (n + 3 < g.N) {
+                if constexpr (OUT_BF16) {
+                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                    *reinterpret_cast<bf16x4 *>(dst) = bf16x4{(__bf16)acc[r][t][0], (__bf16)acc[r][t][1],
+                                                              (__bf16)acc[r][t][2], (__bf16)acc[r][t][3]};
+                } else {
+                    *reinterpret_cast<f32x4 *>(dst) = acc[r][t];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n + i < g.N) dst[i] = (T)acc[r][t][i];
+            }
+        }
 }
 
 // ---- fallback for K not a multiple of 64: one thread per output, exact products ---------------
@@ -910,24 +940,37 @@ int launch_simple(const GemmArgs &g, hipStream_t s)
     return note_launch(hipGetLastError());
 }
 
+// Token tiles by M.  Row tiles per wave, measured on N = 4096 .. 28672: more than one pays only
+// while the grid keeps every CU busy several times over, and not for a single token (whose
+// activations come from L1 anyway).
+template <bool OUT_BF16>
+int launch_skinny(const GemmArgs &g, hipStream_t s)
+{
+    const int mt = (int)((g.M + 15) / 16);
+    const int rt = g.M <= 4 ? 1 : g.N >= 24576 ? 4 : g.N >= 6144 ? 2 : 1;
+    const dim3 grid((unsigned)((g.N + 16 * rt - 1) / (16 * rt))), block(512);
+#define MQ_SKINNY(MT_, RT_) bf16_skinny_kernel<MT_, RT_, (MT_ + RT_ <= 5), OUT_BF16><<<grid, block, 0, s>>>(g)
+#define MQ_SKINNY_RT(MT_) (rt == 4 ? MQ_SKINNY(MT_, 4) : rt == 2 ? MQ_SKINNY(MT_, 2) : MQ_SKINNY(MT_, 1))
+    if (mt == 1)
+        MQ_SKINNY_RT(1);
+    else if (mt == 2)
+        MQ_SKINNY_RT(2);
+    else if (mt == 3)
+        MQ_SKINNY_RT(3);
+    else
+        MQ_SKINNY_RT(4);
+#undef MQ_SKINNY_RT
+#undef MQ_SKINNY
+    return note_launch(hipGetLastError());
+}
+
 template <bool FP4, bool OUT_BF16>
 int launch_any(const GemmArgs &g, hipStream_t s)
 {
     if (g.M == 0 || g.N == 0) return MQ_OK;
     if constexpr (!FP4) {
         // decode shapes: a few tokens against the whole weight matrix
-        if (g.M <= 64 && g.K % 128 == 0 && (g.N + 15) / 16 <= 0x7FFFFFFF) {
-            const dim3 grid((unsigned)((g.N + 15) / 16)), block(512);
-            if (g.M <= 16)
-                bf16_skinny_kernel<1, OUT_BF16><<<grid, block, 0, s>>>(g);
-            else if (g.M <= 32)
-                bf16_skinny_kernel<2, OUT_BF16><<<grid, block, 0, s>>>(g);
-            else if (g.M <= 48)
-                bf16_skinny_kernel<3, OUT_BF16><<<grid, block, 0, s>>>(g);
-            else
-                bf16_skinny_kernel<4, OUT_BF16><<<grid, block, 0, s>>>(g);
-            return note_launch(hipGetLastError());
-        }
+        if (g.M <= 64 && g.K % 128 == 0 && (g.N + 15) / 16 <= 0x7FFFFFFF) return launch_skinny<OUT_BF16>(g, s);
     }
     // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);

@@ -258,7 +258,10 @@ def test_bf16_gemm_against_oracle():
     for M, N, K in [(256, 1024, 1024), (77, 200, 320), (5, 16, 40), (513, 264, 64),
                     # decode shapes (M <= 64, K % 128 == 0): the weight-streaming kernel
                     (1, 4096, 4096), (7, 272, 128), (16, 1000, 1024), (17, 48, 384), (33, 520, 2048),
-                    (49, 16, 256), (64, 264, 14336)]:
+                    (49, 16, 256), (64, 264, 14336),
+                    # ... with two and four row tiles per wave (N >= 6144, N >= 24576), ragged N
+                    (16, 6152, 256), (33, 8200, 384), (64, 8264, 256), (48, 9000, 128), (1, 8192, 1024),
+                    (20, 4096, 2176), (5, 24584, 128), (40, 24640, 256), (64, 24576, 384)]:
         x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
         w = wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32))
         a, b = oracle.bf16_to_f64(x), oracle.bf16_to_f64(w)
