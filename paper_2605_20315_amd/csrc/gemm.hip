@@ -20,7 +20,9 @@
 //                       tile, or a 256x128 tile with K split over wave pairs.
 //   gemm_fp4_pipelined  small NVFP4 problems (128x128 tiles): operands are expanded once per
 //                       workgroup while being staged into LDS.
-//   gemm_bf16_pipelined the BF16 baseline, same LDS pipeline.
+//   gemm_bf16_d2l       the BF16 baseline on large problems: 256x256 tile, four waves of 128x128,
+//                       tiles loaded from global memory straight into LDS.
+//   gemm_bf16_pipelined the BF16 baseline on smaller problems, same LDS pipeline as above.
 //   bf16_skinny_kernel  BF16 with M <= 64 (decode shapes), weight streaming.
 //   gemm_simple_kernel  any K % 16 == 0 / K % 8 == 0 that the tiled kernels do not take.
 //
@@ -552,10 +554,9 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
 
 // ---- BF16 -----------------------------------------------------------------------------------
 
-// Same phases as the NVFP4 kernel.  A tile is fetched into registers right after the barrier of
-// K step t (16 x 128 bits per thread), and written to the free LDS stage during phases 1 and 2
-// of K step t+1.  (Direct global-to-LDS loads were measured slower here: the 64 KB per K step
-// that a BF16 tile pair needs then has to cross the LDS write port within one K step.)
+// Same phases as the NVFP4 LDS pipeline.  A tile is fetched into registers right after the
+// barrier of K step t (16 x 128 bits per thread), and written to the free LDS stage during
+// phases 1 and 2 of K step t+1.  Used for the 256x128 and 128x128 tile configurations.
 template <class C, bool OUT_BF16>
 __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, int tiles_m, int tiles_n)
 {
@@ -668,6 +669,136 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
         kstep(kt + 1, std::integral_constant<int, 1>{});
     }
     if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
+
+    epilogue<C, OUT_BF16>(g, acc, 1.0f, m0, n0, wm0, wn0, frow, fhalf);
+}
+
+// ---- BF16, direct global-to-LDS loads ----------------------------------------------------------
+
+// 256x256x64 tile, four waves of 128x128 (one per SIMD), same LDS layout, phases and barrier as
+// gemm_bf16_pipelined, but the tiles never pass through registers: every wave issues 16
+// global_load_lds_dwordx4 per K step (1 KB each: 8 rows of one operand tile), which write LDS at
+// M0 + 16 * lane.  The bank swizzle is applied on the global side: the lane that fills chunk c' of
+// row r fetches chunk c' ^ key(r).  The loads are written in inline assembly because the compiler
+// orders every LDS read behind all outstanding LDS-writing loads (s_waitcnt vmcnt(0) right after
+// the load), which serialises the pipeline; here the only wait is the one before the barrier.
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, int tiles_n)
+{
+    using C = PCfg<256, 256, 2, 2>;
+    extern __shared__ uint4 lds[];
+    char *const L = reinterpret_cast<char *>(lds);
+    int tm, tn;
+    tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm0 = (wave >> 1) * C::WM, wn0 = (wave & 1) * C::WN;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int KT = (int)(g.K / BK);
+
+    // group u of this wave: rows 8 * (wave * 8 + u) .. + 7 of the A tile (u < 8) or the B tile
+    uint32_t vo[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const bool isA = u < 8;
+        const int r = 8 * (wave * 8 + (u & 7)) + (lane >> 3);
+        int64_t grow = (isA ? m0 : n0) + r;
+        const int64_t total = isA ? g.M : g.N;
+        grow = grow < total ? grow : total - 1;
+        vo[u] = (uint32_t)(grow * (isA ? g.lda : g.ldb) * 2 + (((lane & 7) ^ swz_key(r)) * 16));
+    }
+    // LDS byte address of the dynamic segment
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)L;
+    // load u of tile t: one of this wave's 16 row groups (8 of A, 8 of B) into LDS stage `stage`
+    auto load_group = [&](int t, int stage, int u) {
+        t = t < KT ? t : KT - 1;
+        const char *base = static_cast<const char *>(u < 8 ? g.a : g.b) + (int64_t)t * (BK * 2);
+        const uint32_t dst = lds0 + (u < 8 ? 0 : C::B_BASE) + stage * C::A_STAGE + (wave * 8 + (u & 7)) * 1024;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(dst), "v"(vo[u]), "s"(base)
+                     : "memory");
+    };
+    auto load_tile = [&](int t, int stage) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) load_group(t, stage, u);
+    };
+
+    int fa[4], fb[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        fa[ks] = ((wm0 + frow) * 8 + ((ks * 2 + fhalf) ^ swz_key(frow))) * 16;
+        fb[ks] = C::B_BASE + ((wn0 + frow) * 8 + ((ks * 2 + fhalf) ^ swz_key(frow))) * 16;
+    }
+    uint4 fra[2][C::TM], frb[2][C::TN];
+    auto read_frags = [&](int stage, int ks, uint4(&a)[C::TM], uint4(&b)[C::TN]) {
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+            a[i] = *reinterpret_cast<const uint4 *>(L + fa[ks] + i * 4096 + stage * C::A_STAGE);
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+            b[j] = *reinterpret_cast<const uint4 *>(L + fb[ks] + j * 4096 + stage * C::B_STAGE);
+    };
+    f32x16 acc[C::TM][C::TN];
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    auto mfmas = [&](const uint4(&a)[C::TM], const uint4(&b)[C::TN]) {
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
+    };
+    constexpr int NMFMA = C::TM * C::TN, NREAD = C::TM + C::TN;
+
+    load_tile(0, 0);
+    load_tile(1, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    read_frags(0, 0, fra[0], frb[0]);
+
+    auto kstep = [&](int kt, auto par) {
+        constexpr int cur = decltype(par)::value, nxt = cur ^ 1;
+        read_frags(cur, 1, fra[1], frb[1]);
+        mfmas(fra[0], frb[0]);
+        sched_phase<NMFMA, NREAD, 0, 0, 0>();
+        read_frags(cur, 2, fra[0], frb[0]);
+        mfmas(fra[1], frb[1]);
+        sched_phase<NMFMA, NREAD, 0, 0, 0>();
+        read_frags(cur, 3, fra[1], frb[1]);
+        mfmas(fra[0], frb[0]);
+        sched_phase<NMFMA, NREAD, 0, 0, 0>();
+        // tile kt+1 has landed in this wave's share of stage nxt; after the barrier in everyone's,
+        // and nobody reads stage cur any more: it receives tile kt+2
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        // phase 3, written out: one MFMA, one fragment read (while any remain), one tile load
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {
+            const int i = n >> 2, j = n & 3;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, fra[1][i]), __builtin_bit_cast(bf16x8, frb[1][j]), acc[i][j], 0, 0, 0);
+            if (n < 4)
+                fra[0][n] = *reinterpret_cast<const uint4 *>(L + fa[0] + n * 4096 + nxt * C::A_STAGE);
+            else if (n < 8)
+                frb[0][n - 4] = *reinterpret_cast<const uint4 *>(L + fb[0] + (n - 4) * 4096 + nxt * C::B_STAGE);
+            load_group(kt + 2, cur, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+        kstep(kt, std::integral_constant<int, 0>{});
+        kstep(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the clamped loads past the end still target LDS
 
     epilogue<C, OUT_BF16>(g, acc, 1.0f, m0, n0, wm0, wn0, frow, fhalf);
 }
@@ -975,10 +1106,9 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    using Big = PCfg<256, 256, 2, 4>;   // BF16 only: 8 waves of 128x64, two per SIMD
     using Mid = PCfg<256, 128, 2, 2>;   // BF16 only: 4 waves of 128x64, for one to two rounds of 256x256 tiles
     using Small = PCfg<128, 128, 2, 2>;
-    static std::atomic<bool> cfg_big{false}, cfg_mid{false}, cfg_small{false};
+    static std::atomic<bool> cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
         // Register-direct kernel once 256x128 workgroups fill at least half of the chip: whole
@@ -997,9 +1127,10 @@ int launch_any(const GemmArgs &g, hipStream_t s)
                             cfg_small);
     } else {
         // 256x256 tiles once they fill the 256 CUs at least twice; smaller tiles below that.
+        using D = PCfg<256, 256, 2, 2>;
+        static std::atomic<bool> cfg_d{false};
         if (big_tiles >= 512)
-            return launch_tiles(gemm_bf16_pipelined<Big, OUT_BF16>, Big::LDS_BYTES, 256, 256, Big::THREADS, g, s,
-                                cfg_big);
+            return launch_tiles(gemm_bf16_d2l<OUT_BF16>, D::LDS_BYTES, 256, 256, D::THREADS, g, s, cfg_d);
         if (mid_tiles >= 256)
             return launch_tiles(gemm_bf16_pipelined<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s,
                                 cfg_mid);

@@ -273,6 +273,29 @@ def test_bf16_gemm_against_oracle():
         check_gemm_bf16(y16, ref, na, nb)
 
 
+@pytest.mark.parametrize("K", [64, 192, 320])
+def test_bf16_gemm_large_tiles_with_ragged_edges(K):
+    """16 x 32 tiles of 256x256: the large-tile BF16 kernel, odd and even numbers of K steps."""
+    rng = np.random.default_rng(40 + K)
+    M, N = 256 * 15 + 77, 256 * 31 + 40
+    x = wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    w = wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32))
+    rows = np.unique(np.concatenate([np.arange(0, M, 251), np.arange(M - 80, M), [127, 128, 255, 256, 257]]))
+    a, b = oracle.bf16_to_f64(x[rows]), oracle.bf16_to_f64(w)
+    ref = oracle.gemm_f64(a, b)
+    na, nb = oracle.row_norms(a), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    buf = torch.full((M + 2, N + 8), -7.0, dtype=torch.float32, device="cuda")
+    y32 = mq.bf16_gemm(xd, wd, mq.MQ_OUT_FP32, buf[:M, :N])
+    y16 = mq.bf16_gemm(xd, wd, mq.MQ_OUT_BF16)
+    torch.cuda.synchronize()
+    check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+    check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
+    assert torch.equal(y32.to(torch.bfloat16), y16)
+    assert (buf[M:] == -7.0).all() and (buf[:, N:] == -7.0).all()
+
+
 def test_gemm_errors_and_empty():
     from paper_2605_20315_amd import _lib
     lib = _lib.load()
