@@ -300,7 +300,7 @@ def main() -> int:
             # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated on a plain
             # 1 GiB copy) + WRITE_SIZE (x1.0), averaged over the four launches of a step
             # (profiles/nvfp4_gemm_bf16_gemm_quantizer_llama8b_m8192.md)
-            "traffic": 0.535 * 2 ** 30 if args.config == 2 else None,
+            "traffic": 0.540 * 2 ** 30 if args.config == 2 else None,
         },
     }
 
