@@ -19,5 +19,7 @@ from .ref import (  # noqa: F401
     global_scale,
     num_threads,
     quantize,
+    rmsnorm_f64,
     row_norms,
+    silu_mul_f64,
 )

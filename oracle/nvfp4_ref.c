@@ -216,6 +216,51 @@ void nvfp4_ref_bf16_to_f64(const uint16_t *x, int64_t rows, int64_t K, int64_t l
         for (k = 0; k < K; ++k) out[r * K + k] = (double)bf16_bits_to_float(x[r * ldx + k]);
 }
 
+/* ---------- producers of the quantizer's input --------------------------------------- */
+
+/* The paper quantizes "activations" (Section 3.3) and lets the backend fuse the quantizer
+ * with its neighbours; it does not define the operations that produce those activations.
+ * In the decoder blocks of the models it evaluates (Section 4.1) the inputs of the four
+ * linear layers come from two of them, stated here by their textbook definitions in
+ * binary64.  A fused "producer -> quantize" kernel is checked against
+ * nvfp4_ref_quantize(BF16(producer)): the producer's value rounded once to BF16, which is the
+ * tensor an unfused pipeline would have stored. */
+
+/* Gated-MLP activation feeding the down projection: out[r, k] = silu(g) * u with
+ * g = gate_up[r, k], u = gate_up[r, K + k], silu(g) = g / (1 + exp(-g)).
+ * gate_up: [rows, 2K] BF16, row stride ld; out: [rows, K] binary64, dense. */
+void nvfp4_ref_silu_mul_f64(const uint16_t *gate_up, int64_t rows, int64_t K, int64_t ld, double *out)
+{
+    int64_t r, k;
+#pragma omp parallel for schedule(static) private(k)
+    for (r = 0; r < rows; ++r)
+        for (k = 0; k < K; ++k) {
+            double g = (double)bf16_bits_to_float(gate_up[r * ld + k]);
+            double u = (double)bf16_bits_to_float(gate_up[r * ld + K + k]);
+            out[r * K + k] = g / (1.0 + exp(-g)) * u;
+        }
+}
+
+/* Root-mean-square normalisation feeding the qkv and gate_up projections:
+ * out[r, k] = x[r, k] / sqrt(mean_k(x[r, :]^2) + eps) * w[k].
+ * x: [rows, K] BF16, row stride ldx; w: [K] BF16; out: [rows, K] binary64, dense. */
+void nvfp4_ref_rmsnorm_f64(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const uint16_t *w,
+                           double eps, double *out)
+{
+    int64_t r, k;
+#pragma omp parallel for schedule(static) private(k)
+    for (r = 0; r < rows; ++r) {
+        double ss = 0.0, d;
+        for (k = 0; k < K; ++k) {
+            double v = (double)bf16_bits_to_float(x[r * ldx + k]);
+            ss += v * v;
+        }
+        d = sqrt(ss / (double)K + eps);
+        for (k = 0; k < K; ++k)
+            out[r * K + k] = (double)bf16_bits_to_float(x[r * ldx + k]) / d * (double)bf16_bits_to_float(w[k]);
+    }
+}
+
 /* ---------- GEMM: the plain definition ---------------------------------------------- */
 
 /* y[m, n] = sum_{k ascending} a[m, k] * b[n, k] in binary64; a: [M, K], b: [N, K],

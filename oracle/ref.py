@@ -49,6 +49,8 @@ def _load():
         "nvfp4_ref_dequantize": (ctypes.c_int, [vp, vp, f32, i64, i64, vp]),
         "nvfp4_ref_bf16_to_f64": (None, [vp, i64, i64, i64, vp]),
         "nvfp4_ref_gemm_f64": (None, [vp, vp, i64, i64, i64, vp]),
+        "nvfp4_ref_silu_mul_f64": (None, [vp, i64, i64, i64, vp]),
+        "nvfp4_ref_rmsnorm_f64": (None, [vp, i64, i64, i64, vp, f64, vp]),
         "nvfp4_ref_row_norms": (None, [vp, i64, i64, vp]),
         "nvfp4_ref_bf16_round_array": (None, [vp, i64, vp]),
         "nvfp4_ref_num_threads": (ctypes.c_int, []),
@@ -132,6 +134,25 @@ def bf16_to_f64(x_bf16: np.ndarray) -> np.ndarray:
     rows, K, ld = _rows_k_ld(x_bf16)
     out = np.empty((rows, K), dtype=np.float64)
     _load().nvfp4_ref_bf16_to_f64(_ptr(x_bf16), rows, K, ld, _ptr(out))
+    return out
+
+
+def silu_mul_f64(gate_up_bf16: np.ndarray) -> np.ndarray:
+    """silu(gate) * up in binary64; gate = columns [0, K), up = columns [K, 2K) of a [rows, 2K] BF16 array."""
+    assert gate_up_bf16.dtype == np.uint16 and gate_up_bf16.shape[1] % 2 == 0
+    rows, k2, ld = _rows_k_ld(gate_up_bf16)
+    out = np.empty((rows, k2 // 2), dtype=np.float64)
+    _load().nvfp4_ref_silu_mul_f64(_ptr(gate_up_bf16), rows, k2 // 2, ld, _ptr(out))
+    return out
+
+
+def rmsnorm_f64(x_bf16: np.ndarray, w_bf16: np.ndarray, eps: float) -> np.ndarray:
+    """x / sqrt(mean(x^2) + eps) * w per row, in binary64; x [rows, K] and w [K] are BF16 bit patterns."""
+    assert x_bf16.dtype == np.uint16 and w_bf16.dtype == np.uint16 and w_bf16.shape == (x_bf16.shape[1],)
+    rows, K, ld = _rows_k_ld(x_bf16)
+    w = np.ascontiguousarray(w_bf16)
+    out = np.empty((rows, K), dtype=np.float64)
+    _load().nvfp4_ref_rmsnorm_f64(_ptr(x_bf16), rows, K, ld, _ptr(w), float(eps), _ptr(out))
     return out
 
 
