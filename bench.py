@@ -199,6 +199,42 @@ def main() -> int:
         torch.cuda.synchronize()
         decode[f"M={md}"] = round(20 * w_bytes / (g0.elapsed_time(g1) * 1e-3) * 1e-9, 1)
 
+    # ---- producer-fused quantizers (the quantizer fused with its neighbour, Section 3.3): the two
+    # activations of a decoder block that are quantized, against producer (torch) + nvfp4_quantize ----
+    fused = None
+    if args.config == 2:
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            f0.record()
+            for _ in range(reps):
+                fn()
+            f1.record()
+            torch.cuda.synchronize()
+            return f0.elapsed_time(f1) / reps
+        Kd, Kh = 14336, 4096
+        gu = torch.randn((M, 2 * Kd), dtype=torch.bfloat16, device="cuda")
+        xh = torch.randn((M, Kh), dtype=torch.bfloat16, device="cuda")
+        gw = torch.ones(Kh, dtype=torch.bfloat16, device="cuda")
+        a1 = torch.full((1,), 30.0 / 2688.0, dtype=torch.float32, device="cuda")
+        cd = torch.empty((M, Kd // 2), dtype=torch.uint8, device="cuda")
+        sd = torch.empty((M, Kd // 16), dtype=torch.uint8, device="cuda")
+        ch = torch.empty((M, Kh // 2), dtype=torch.uint8, device="cuda")
+        sh = torch.empty((M, Kh // 16), dtype=torch.uint8, device="cuda")
+        t_f1 = timed(lambda: mq.nvfp4_quantize_silu_mul(gu, a1, cd, sd, LAYOUT))
+        t_u1 = timed(lambda: mq.nvfp4_quantize(torch.nn.functional.silu(gu[:, :Kd]) * gu[:, Kd:], a1, cd, sd, LAYOUT))
+        t_f2 = timed(lambda: mq.nvfp4_quantize_rmsnorm(xh, gw, 1e-6, a1, ch, sh, LAYOUT))
+        t_u2 = timed(lambda: mq.nvfp4_quantize(torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6), a1, ch, sh, LAYOUT))
+        fused = {
+            "silu_mul_quantize": {"shape": [M, Kd], "fused_ms": round(t_f1, 4), "producer_then_quantize_ms": round(t_u1, 4),
+                                  "fused_gbs": round((4.0 + QUANT_BYTES_PER_ELT - 2.0) * M * Kd / (t_f1 * 1e-3) * 1e-9, 1)},
+            "rmsnorm_quantize": {"shape": [M, Kh], "fused_ms": round(t_f2, 4), "producer_then_quantize_ms": round(t_u2, 4),
+                                 "fused_gbs": round(QUANT_BYTES_PER_ELT * M * Kh / (t_f2 * 1e-3) * 1e-9, 1)},
+        }
+        del gu, xh, cd, sd, ch, sh
+        torch.cuda.empty_cache()
+
     # ---- second workload: the paper's sweep axis (Section 4.4, Fig. 3: prefill speed-up over BF16
     # against context length / batch), as tokens M per prefill batch on the same layer set.
     # Activations are generated on the device (N(0,1), 0.1 % of the channels scaled by 20: the
@@ -279,6 +315,7 @@ def main() -> int:
         "global_scale_gbs": round(amax_gbs, 1),
         "decode_bf16_gemm_weight_gbs": decode,
         "tokens_per_batch_sweep": sweep,
+        "fused_producer_quantizers": fused,
         "quantizer_gbs": round(quant_gbs, 1),
         "quantizer_pct_of_hbm_peak": round(100.0 * quant_gbs / PEAK_HBM_GBS, 1),
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}

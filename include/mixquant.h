@@ -99,6 +99,34 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
                    void *stream);
 
 /*
+ * Quantizer fused with the operation that produces the activation ("quantization ... can be
+ * fused efficiently by the backend", Section 3.3).  The paper does not define the producers;
+ * these are the two that feed the linear layers of the decoder blocks of the models it
+ * evaluates (Section 4.1), by their textbook definitions.  In both, the producer's value is
+ * computed in binary32, rounded once to BF16 (nearest even), and that BF16 tensor is quantized
+ * exactly as nvfp4_quantize would: the BF16 activations never travel through memory.
+ * p_bf16 / y_bf16 (may be NULL): if given, also receives the BF16 tensor that was quantized,
+ * [rows, K] with row stride ldp / ldy elements (multiple of 8, 16-byte aligned base); the codes
+ * and scales are then bit-identical to nvfp4_quantize applied to it.
+ *
+ * nvfp4_quantize_silu_mul: gated-MLP activation, the input of the down projection.
+ *    p[r, k] = silu(g) * u,  g = gate_up[r, k],  u = gate_up[r, K + k],  silu(g) = g / (1 + exp(-g))
+ * gate_up_bf16: [rows, 2K] BF16, row stride ld elements (ld >= 2K, ld % 8 == 0).  Gates below
+ * about -88 (exp(-g) overflows binary32) give -0, as any binary32 evaluation does.
+ * nvfp4_quantize_rmsnorm: root-mean-square normalisation, the input of the qkv and gate_up
+ * projections.
+ *    y[r, k] = x[r, k] / sqrt(mean_k(x[r, :]^2) + eps) * w[k]
+ * x_bf16: [rows, K] BF16, row stride ldx; w_bf16: [K] BF16; eps >= 0; K % 64 == 0.
+ * Other arguments, alignment and errors as in nvfp4_quantize.
+ */
+int nvfp4_quantize_silu_mul(const void *gate_up_bf16, int64_t rows, int64_t K, int64_t ld,
+                            const float *alpha_dev, uint8_t *codes, uint8_t *scales, int layout,
+                            void *p_bf16, int64_t ldp, void *stream);
+int nvfp4_quantize_rmsnorm(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, const void *w_bf16,
+                           float eps, const float *alpha_dev, uint8_t *codes, uint8_t *scales,
+                           int layout, void *y_bf16, int64_t ldy, void *stream);
+
+/*
  * Offline weight pre-pack (weights are static across requests, Section 3.3 "Prefill-Decode
  * Disaggregation Deployment"): copy an NVFP4 tensor from one mq_layout to the other.  Pure byte
  * permutation by the index map given at mq_layout; src and dst must not overlap.

@@ -12,5 +12,7 @@ from .ops import (  # noqa: F401
     nvfp4_global_scale,
     nvfp4_linear,
     nvfp4_quantize,
+    nvfp4_quantize_rmsnorm,
+    nvfp4_quantize_silu_mul,
     nvfp4_relayout,
 )

@@ -39,6 +39,10 @@ def load() -> ctypes.CDLL:
     lib.nvfp4_global_scale.argtypes = [vp, i64, i64, i64, vp, vp]
     lib.nvfp4_quantize.restype = ci
     lib.nvfp4_quantize.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp]
+    lib.nvfp4_quantize_silu_mul.restype = ci
+    lib.nvfp4_quantize_silu_mul.argtypes = [vp, i64, i64, i64, vp, vp, vp, ci, vp, i64, vp]
+    lib.nvfp4_quantize_rmsnorm.restype = ci
+    lib.nvfp4_quantize_rmsnorm.argtypes = [vp, i64, i64, i64, vp, ctypes.c_float, vp, vp, vp, ci, vp, i64, vp]
     lib.nvfp4_relayout.restype = ci
     lib.nvfp4_relayout.argtypes = [vp, vp, vp, vp, i64, i64, ci, ci, vp]
     lib.nvfp4_gemm.restype = ci

@@ -58,6 +58,50 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, con
                            static_cast<hipStream_t>(stream));
 }
 
+static int check_quant_out(int64_t rows, int64_t K, const float *alpha_dev, const uint8_t *codes,
+                           const uint8_t *scales, int layout, const void *dbg, int64_t ldd)
+{
+    if (layout != MQ_LAYOUT_LINEAR && layout != MQ_LAYOUT_KTILE) return MQ_ERR_ARG;
+    if (rows < 0 || K <= 0 || K % kBlock != 0) return MQ_ERR_SHAPE;
+    if (layout == MQ_LAYOUT_KTILE && K % 64 != 0) return MQ_ERR_SHAPE;
+    if (dbg && ldd < K) return MQ_ERR_SHAPE;
+    if (rows == 0) return MQ_OK;
+    if (!alpha_dev || !codes || !scales) return MQ_ERR_NULL;
+    if (!aligned(codes, 16) || !aligned(alpha_dev, 4)) return MQ_ERR_ALIGN;
+    if (layout == MQ_LAYOUT_KTILE && !aligned(scales, 4)) return MQ_ERR_ALIGN;
+    if (dbg && (!aligned(dbg, 16) || ldd % 8 != 0)) return MQ_ERR_ALIGN;
+    return MQ_OK;
+}
+
+int nvfp4_quantize_silu_mul(const void *gate_up_bf16, int64_t rows, int64_t K, int64_t ld, const float *alpha_dev,
+                            uint8_t *codes, uint8_t *scales, int layout, void *p_bf16, int64_t ldp, void *stream)
+{
+    if (K > 0 && ld < 2 * K) return MQ_ERR_SHAPE;
+    if (int rc = check_quant_out(rows, K, alpha_dev, codes, scales, layout, p_bf16, ldp)) return rc;
+    if (rows == 0) return MQ_OK;
+    if (!gate_up_bf16) return MQ_ERR_NULL;
+    if (!aligned(gate_up_bf16, 16) || ld % 8 != 0) return MQ_ERR_ALIGN;
+    return launch_quantize_silu_mul(static_cast<const uint16_t *>(gate_up_bf16), rows, K, ld, alpha_dev, codes,
+                                    scales, layout, static_cast<uint16_t *>(p_bf16), ldp,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_quantize_rmsnorm(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx, const void *w_bf16, float eps,
+                           const float *alpha_dev, uint8_t *codes, uint8_t *scales, int layout, void *y_bf16,
+                           int64_t ldy, void *stream)
+{
+    if (K > 0 && K % 64 != 0) return MQ_ERR_SHAPE;
+    if (!(eps >= 0.0f) || eps > 3.0e38f) return MQ_ERR_ARG;
+    if (int rc = check_quant_out(rows, K, alpha_dev, codes, scales, layout, y_bf16, ldy)) return rc;
+    if (ldx < K) return MQ_ERR_SHAPE;
+    if (rows == 0) return MQ_OK;
+    if (!x_bf16 || !w_bf16) return MQ_ERR_NULL;
+    if (!aligned(x_bf16, 16) || !aligned(w_bf16, 16) || ldx % 8 != 0) return MQ_ERR_ALIGN;
+    return launch_quantize_rmsnorm(static_cast<const uint16_t *>(x_bf16), rows, K, ldx,
+                                   static_cast<const uint16_t *>(w_bf16), eps, alpha_dev, codes, scales, layout,
+                                   static_cast<uint16_t *>(y_bf16), ldy, static_cast<hipStream_t>(stream));
+}
+
 int nvfp4_relayout(const uint8_t *src_codes, const uint8_t *src_scales, uint8_t *dst_codes, uint8_t *dst_scales,
                    int64_t rows, int64_t K, int from_layout, int to_layout, void *stream)
 {

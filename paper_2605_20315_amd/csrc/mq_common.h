@@ -26,6 +26,13 @@ int launch_global_scale(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx,
 int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
                     uint8_t *codes, uint8_t *scales, int layout, hipStream_t s);
 
+// producer-fused quantizers (p / y: optional BF16 output of the producer, may be null)
+int launch_quantize_silu_mul(const uint16_t *gate_up, int64_t rows, int64_t K, int64_t ld, const float *alpha,
+                             uint8_t *codes, uint8_t *scales, int layout, uint16_t *p, int64_t ldp, hipStream_t s);
+int launch_quantize_rmsnorm(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const uint16_t *w, float eps,
+                            const float *alpha, uint8_t *codes, uint8_t *scales, int layout, uint16_t *y,
+                            int64_t ldy, hipStream_t s);
+
 int launch_relayout(const uint8_t *src_c, const uint8_t *src_s, uint8_t *dst_c, uint8_t *dst_s, int64_t rows,
                     int64_t K, bool to_ktile, hipStream_t s);
 

@@ -49,39 +49,19 @@ __device__ __forceinline__ uint32_t pack_pair(uint32_t packed, uint32_t w, float
     return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(packed, y0, y1, 1.0f, SEL);
 }
 
-// One lane per 16-element block.  CONTIG: ldx == K, so block g starts at element 16*g.
-template <bool CONTIG>
-__global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__restrict__ x,
-                                                            int64_t total_blocks, int blocks_per_row,
-                                                            int64_t ldx,
-                                                            const float *__restrict__ alpha_p,
-                                                            uint8_t *__restrict__ codes,
-                                                            uint8_t *__restrict__ scales)
+// Eq. 2 then Eq. 1 for one block of 16 BF16 values (v0: elements 0..7, v1: 8..15, two per dword):
+// scale byte and two dwords of packed codes.  Every step IEEE binary32, nearest-even, unfused.
+__device__ __forceinline__ void quantize_block16(uint4 v0, uint4 v1, float alpha, float d6, uint32_t &c0,
+                                                 uint32_t &c1, int &sb)
 {
-    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (g >= total_blocks) return;
-    const float alpha = *alpha_p;
-    const float d6 = 6.0f * alpha;  // alpha * q_max
-    const uint16_t *src;
-    if (CONTIG) {
-        src = x + g * kBlock;
-    } else {
-        const int64_t row = g / blocks_per_row;
-        const int64_t b = g - row * blocks_per_row;
-        src = x + row * ldx + b * kBlock;
-    }
-    const uint4 v0 = reinterpret_cast<const uint4 *>(src)[0];
-    const uint4 v1 = reinterpret_cast<const uint4 *>(src)[1];
-
     const float amax = __uint_as_float(amax16_bits(v0, v1) << 16);
     float s = amax / d6;                                     // Eq. 2 argument (IEEE division)
     s = fminf(s, 448.0f);                                    // saturation of Pi_E4M3
-    const int sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;  // Pi_E4M3
+    sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;  // Pi_E4M3
     const float sigma = __builtin_amdgcn_cvt_pk_f32_fp8(sb, false)[0];
     const float t = alpha * sigma;
     const float r = (sigma == 0.0f) ? 0.0f : 1.0f / t;       // IEEE division
-
-    uint32_t c0 = 0, c1 = 0;
+    c0 = c1 = 0;
     c0 = pack_pair<0>(c0, v0.x, r);
     c0 = pack_pair<1>(c0, v0.y, r);
     c0 = pack_pair<2>(c0, v0.z, r);
@@ -90,7 +70,82 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
     c1 = pack_pair<1>(c1, v1.y, r);
     c1 = pack_pair<2>(c1, v1.z, r);
     c1 = pack_pair<3>(c1, v1.w, r);
+}
 
+// ---- where a block's 16 BF16 values come from ---------------------------------------------------
+
+// The tensor itself.
+struct PlainSrc {
+    const uint16_t *x;
+    int64_t ldx;
+    __device__ __forceinline__ void load(int64_t row, int64_t col, uint4 &v0, uint4 &v1) const
+    {
+        const uint4 *src = reinterpret_cast<const uint4 *>(x + row * ldx + col);
+        v0 = src[0];
+        v1 = src[1];
+    }
+};
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)  // nearest-even, element 2i in the low half
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+
+// The gated-MLP activation silu(gate) * up of a [rows, 2K] tensor (gate = columns [0, K), up =
+// columns [K, 2K)), computed in binary32 and rounded once to BF16: the tensor an unfused
+// pipeline would have stored and read back.  silu(g) = g / (1 + exp(-g)) with the hardware
+// exponential (about 1 ulp: far inside half a BF16 ulp except within 1e-4 of a rounding
+// boundary) and an IEEE division, which keeps the tiny quotients of strongly negative gates
+// (the approximate reciprocal flushes them to zero).  Below about -88 exp(-g) overflows and the
+// result is -0.  p, when not null, receives the BF16 values (checking aid).
+struct SiluMulSrc {
+    const uint16_t *gu;
+    int64_t ld, K;
+    uint16_t *p;
+    int64_t ldp;
+    static __device__ __forceinline__ uint32_t pair(uint32_t g, uint32_t u)
+    {
+        const float g0 = __uint_as_float(g << 16), g1 = __uint_as_float(g & 0xFFFF0000u);
+        const float u0 = __uint_as_float(u << 16), u1 = __uint_as_float(u & 0xFFFF0000u);
+        const float s0 = g0 / (1.0f + __expf(-g0));
+        const float s1 = g1 / (1.0f + __expf(-g1));
+        return pack_bf16(s0 * u0, s1 * u1);
+    }
+    __device__ __forceinline__ void load(int64_t row, int64_t col, uint4 &v0, uint4 &v1) const
+    {
+        const uint4 *gs = reinterpret_cast<const uint4 *>(gu + row * ld + col);
+        const uint4 *us = reinterpret_cast<const uint4 *>(gu + row * ld + K + col);
+        const uint4 g0 = gs[0], g1 = gs[1], u0 = us[0], u1 = us[1];
+        v0 = make_uint4(pair(g0.x, u0.x), pair(g0.y, u0.y), pair(g0.z, u0.z), pair(g0.w, u0.w));
+        v1 = make_uint4(pair(g1.x, u1.x), pair(g1.y, u1.y), pair(g1.z, u1.z), pair(g1.w, u1.w));
+        if (p) {
+            uint4 *dst = reinterpret_cast<uint4 *>(p + row * ldp + col);
+            dst[0] = v0;
+            dst[1] = v1;
+        }
+    }
+};
+
+// One lane per 16-element block, canonical (linear) output.
+template <class Src>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(Src src, int64_t total_blocks, int blocks_per_row,
+                                                            const float *__restrict__ alpha_p,
+                                                            uint8_t *__restrict__ codes,
+                                                            uint8_t *__restrict__ scales)
+{
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (g >= total_blocks) return;
+    const float alpha = *alpha_p;
+    const float d6 = 6.0f * alpha;  // alpha * q_max
+    const int64_t row = g / blocks_per_row;
+    const int64_t b = g - row * blocks_per_row;
+    uint4 v0, v1;
+    src.load(row, b * kBlock, v0, v1);
+    uint32_t c0, c1;
+    int sb;
+    quantize_block16(v0, v1, alpha, d6, c0, c1, sb);
     reinterpret_cast<uint2 *>(codes)[g] = make_uint2(c0, c1);  // dense [rows, K/2]: 8 bytes per block
     scales[g] = (uint8_t)sb;                                   // dense [rows, K/16]
 }
@@ -100,14 +155,29 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
 // 2 KB contiguous per row (lane l: K step l/4, block l%4).  The codes and scale bytes go through
 // LDS so that writing is contiguous too: per K step 16 rows x 32 code bytes = 512 bytes and
 // 16 x 4 scale bytes = 64 bytes.
-__global__ __launch_bounds__(kThreads) void quantize_ktile_kernel(const uint16_t *__restrict__ x, int64_t rows,
-                                                                  int64_t row_base, int ksteps, int64_t ldx,
-                                                                  const float *__restrict__ alpha_p,
+constexpr int T_STRIDE = 16 * 4 + 4;  // uint2 units per K step in LDS, padded against bank conflicts
+
+// Second half of the transposition: thread (K step ot, row orow) writes one unit of 32 + 4 bytes.
+__device__ __forceinline__ void write_ktile_unit(const uint2 *lc, const uint8_t (*ls)[16][4], int t0, int64_t r0,
+                                                 int ksteps, int64_t rows, uint8_t *codes, uint8_t *scales)
+{
+    const int ot = (threadIdx.x >> 4) & 15, orow = threadIdx.x & 15;  // 256 consecutive threads: one unit each
+    if (t0 + ot < ksteps && r0 + orow < rows) {
+        const int64_t slot = (int64_t)(t0 + ot) * rows + r0 + orow;
+        const uint2 *p = &lc[ot * T_STRIDE + orow * 4];
+        reinterpret_cast<uint4 *>(codes)[slot * 2] = make_uint4(p[0].x, p[0].y, p[1].x, p[1].y);
+        reinterpret_cast<uint4 *>(codes)[slot * 2 + 1] = make_uint4(p[2].x, p[2].y, p[3].x, p[3].y);
+        reinterpret_cast<uint32_t *>(scales)[slot] = *reinterpret_cast<const uint32_t *>(&ls[ot][orow][0]);
+    }
+}
+
+template <class Src>
+__global__ __launch_bounds__(kThreads) void quantize_ktile_kernel(Src src, int64_t rows, int64_t row_base,
+                                                                  int ksteps, const float *__restrict__ alpha_p,
                                                                   uint8_t *__restrict__ codes,
                                                                   uint8_t *__restrict__ scales)
 {
-    constexpr int T_STRIDE = 16 * 4 + 4;        // uint2 units per K step in LDS, padded against bank conflicts
-    __shared__ uint2 lc[16 * T_STRIDE];         // [K step][row][block]
+    __shared__ uint2 lc[16 * T_STRIDE];  // [K step][row][block]
     __shared__ uint8_t ls[16][16][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t0 = blockIdx.x * 16;
@@ -120,37 +190,146 @@ __global__ __launch_bounds__(kThreads) void quantize_ktile_kernel(const uint16_t
         const int rl = wave * 4 + it;
         const int64_t row = r0 + rl;
         if (row < rows && t0 + tl < ksteps) {
-            const uint16_t *src = x + row * ldx + (int64_t)(t0 + tl) * 64 + blk * kBlock;
-            const uint4 v0 = reinterpret_cast<const uint4 *>(src)[0];
-            const uint4 v1 = reinterpret_cast<const uint4 *>(src)[1];
-            const float amax = __uint_as_float(amax16_bits(v0, v1) << 16);
-            float s = amax / d6;
-            s = fminf(s, 448.0f);
-            const int sb = __builtin_amdgcn_cvt_pk_fp8_f32(s, 0.0f, 0, false) & 0xFF;
-            const float sigma = __builtin_amdgcn_cvt_pk_f32_fp8(sb, false)[0];
-            const float tt = alpha * sigma;
-            const float r = (sigma == 0.0f) ? 0.0f : 1.0f / tt;
-            uint32_t c0 = 0, c1 = 0;
-            c0 = pack_pair<0>(c0, v0.x, r);
-            c0 = pack_pair<1>(c0, v0.y, r);
-            c0 = pack_pair<2>(c0, v0.z, r);
-            c0 = pack_pair<3>(c0, v0.w, r);
-            c1 = pack_pair<0>(c1, v1.x, r);
-            c1 = pack_pair<1>(c1, v1.y, r);
-            c1 = pack_pair<2>(c1, v1.z, r);
-            c1 = pack_pair<3>(c1, v1.w, r);
+            uint4 v0, v1;
+            src.load(row, (int64_t)(t0 + tl) * 64 + blk * kBlock, v0, v1);
+            uint32_t c0, c1;
+            int sb;
+            quantize_block16(v0, v1, alpha, d6, c0, c1, sb);
             lc[tl * T_STRIDE + rl * 4 + blk] = make_uint2(c0, c1);
             ls[tl][rl][blk] = (uint8_t)sb;
         }
     }
     __syncthreads();
-    const int ot = threadIdx.x >> 4, orow = threadIdx.x & 15;   // output unit: (K step, row)
-    if (t0 + ot < ksteps && r0 + orow < rows) {
-        const int64_t slot = (int64_t)(t0 + ot) * rows + r0 + orow;
-        const uint2 *p = &lc[ot * T_STRIDE + orow * 4];
-        reinterpret_cast<uint4 *>(codes)[slot * 2] = make_uint4(p[0].x, p[0].y, p[1].x, p[1].y);
-        reinterpret_cast<uint4 *>(codes)[slot * 2 + 1] = make_uint4(p[2].x, p[2].y, p[3].x, p[3].y);
-        reinterpret_cast<uint32_t *>(scales)[slot] = *reinterpret_cast<const uint32_t *>(&ls[ot][orow][0]);
+    write_ktile_unit(lc, ls, t0, r0, ksteps, rows, codes, scales);
+}
+
+// ---- RMS normalisation fused with the quantizer ----------------------------------------------
+
+// y[r, k] = x[r, k] / sqrt(mean_k x[r, :]^2 + eps) * w[k] in binary32 (sum of squares: each lane
+// adds its elements in ascending k, then a butterfly over the wave), rounded once to BF16, then
+// quantized as above.  A workgroup of 16 waves owns 16 rows and all of K, one wave per row, so a
+// row's sum is a reduction over one wave.  Lane l takes K step c*16 + l/4, block l%4 of chunk c
+// (16 K steps = 1024 columns), as in the K-step-major quantizer.
+// NC > 0: the row (NC chunks: 8 registers each) stays in registers between the two passes, so x
+// is read once; NC == 0: any K, x is read again in the second pass (from cache).
+// y_out, when not null, receives the BF16 values (checking aid).
+constexpr int kRmsThreads = 1024;
+
+template <int NC, bool KTILE_OUT>
+__global__ __launch_bounds__(kRmsThreads) void rmsnorm_quantize_kernel(const uint16_t *__restrict__ x, int64_t rows,
+                                                                       int ksteps, int64_t ldx,
+                                                                       const uint16_t *__restrict__ w, float eps,
+                                                                       float inv_k,
+                                                                       const float *__restrict__ alpha_p,
+                                                                       uint8_t *__restrict__ codes,
+                                                                       uint8_t *__restrict__ scales,
+                                                                       uint16_t *__restrict__ y_out, int64_t ldy)
+{
+    constexpr int NCR = NC > 0 ? NC : 1;
+    // K-step-major output: NC > 0 stages all chunks and synchronises once, NC == 0 chunk by chunk
+    __shared__ uint2 lc[NCR][16 * T_STRIDE];
+    __shared__ uint8_t ls[NCR][16][16][4];
+    const int lane = threadIdx.x & 63, rl = threadIdx.x >> 6;  // rl: row within the group = wave
+    const int64_t r0 = (int64_t)blockIdx.x * 16, row = r0 + rl;
+    const bool row_ok = row < rows;
+    const float alpha = *alpha_p;
+    const float d6 = 6.0f * alpha;
+    const int tl = lane >> 2, blk = lane & 3;
+    const int chunks = (ksteps + 15) / 16;
+    const PlainSrc src{x, ldx};
+
+    auto sumsq = [](uint4 v0, uint4 v1) {
+        const uint32_t d[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float a = __uint_as_float(d[i] << 16), b = __uint_as_float(d[i] & 0xFFFF0000u);
+            s += a * a;
+            s += b * b;
+        }
+        return s;
+    };
+    uint4 keep[NCR][2];
+    float ss = 0.0f;
+    if constexpr (NC > 0) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int t = c * 16 + tl;
+            uint4 v0 = make_uint4(0, 0, 0, 0), v1 = v0;
+            if (row_ok && t < ksteps) src.load(row, (int64_t)t * 64 + blk * kBlock, v0, v1);
+            keep[c][0] = v0;
+            keep[c][1] = v1;
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) ss += sumsq(keep[c][0], keep[c][1]);
+    } else {
+        for (int c = 0; c < chunks; ++c) {
+            const int t = c * 16 + tl;
+            if (row_ok && t < ksteps) {
+                uint4 v0, v1;
+                src.load(row, (int64_t)t * 64 + blk * kBlock, v0, v1);
+                ss += sumsq(v0, v1);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+    const float iv = __builtin_amdgcn_rsqf(ss * inv_k + eps);
+
+    auto norm_pair = [](uint32_t xv, uint32_t wv, float inv) {
+        const float a = __uint_as_float(xv << 16) * inv, b = __uint_as_float(xv & 0xFFFF0000u) * inv;
+        return pack_bf16(a * __uint_as_float(wv << 16), b * __uint_as_float(wv & 0xFFFF0000u));
+    };
+    auto chunk = [&](int c, uint4 x0, uint4 x1) {
+        const int t = c * 16 + tl;
+        if (row_ok && t < ksteps) {
+            const uint4 *ws = reinterpret_cast<const uint4 *>(w + (int64_t)t * 64 + blk * kBlock);
+            const uint4 w0 = ws[0], w1 = ws[1];
+            const uint4 v0 = make_uint4(norm_pair(x0.x, w0.x, iv), norm_pair(x0.y, w0.y, iv),
+                                        norm_pair(x0.z, w0.z, iv), norm_pair(x0.w, w0.w, iv));
+            const uint4 v1 = make_uint4(norm_pair(x1.x, w1.x, iv), norm_pair(x1.y, w1.y, iv),
+                                        norm_pair(x1.z, w1.z, iv), norm_pair(x1.w, w1.w, iv));
+            if (y_out) {
+                uint4 *dst = reinterpret_cast<uint4 *>(y_out + row * ldy + (int64_t)t * 64 + blk * kBlock);
+                dst[0] = v0;
+                dst[1] = v1;
+            }
+            uint32_t c0, c1;
+            int sb;
+            quantize_block16(v0, v1, alpha, d6, c0, c1, sb);
+            if constexpr (KTILE_OUT) {
+                const int slot = NC > 0 ? c : 0;
+                lc[slot][tl * T_STRIDE + rl * 4 + blk] = make_uint2(c0, c1);
+                ls[slot][tl][rl][blk] = (uint8_t)sb;
+            } else {
+                const int64_t g = row * ((int64_t)ksteps * 4) + (int64_t)t * 4 + blk;
+                reinterpret_cast<uint2 *>(codes)[g] = make_uint2(c0, c1);
+                scales[g] = (uint8_t)sb;
+            }
+        }
+        if constexpr (KTILE_OUT && NC == 0) {
+            __syncthreads();
+            if (threadIdx.x < 256) write_ktile_unit(lc[0], ls[0], c * 16, r0, ksteps, rows, codes, scales);
+            __syncthreads();
+        }
+    };
+    if constexpr (NC > 0) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            if (c < chunks) chunk(c, keep[c][0], keep[c][1]);  // uniform
+        if constexpr (KTILE_OUT) {
+            __syncthreads();
+#pragma unroll
+            for (int c = (int)(threadIdx.x >> 8); c < NC; c += kRmsThreads / 256)
+                if (c < chunks) write_ktile_unit(lc[c], ls[c], c * 16, r0, ksteps, rows, codes, scales);
+        }
+    } else {
+        for (int c = 0; c < chunks; ++c) {
+            const int t = c * 16 + tl;
+            uint4 x0 = make_uint4(0, 0, 0, 0), x1 = x0;
+            if (row_ok && t < ksteps) src.load(row, (int64_t)t * 64 + blk * kBlock, x0, x1);
+            chunk(c, x0, x1);
+        }
     }
 }
 
@@ -239,8 +418,11 @@ __global__ void amax_final_kernel(uint32_t *acc)
 
 }  // namespace
 
-int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
-                    uint8_t *codes, uint8_t *scales, int layout, hipStream_t s)
+namespace {
+
+template <class Src>
+int launch_quantize_from(const Src &src, int64_t rows, int64_t K, const float *alpha, uint8_t *codes,
+                         uint8_t *scales, int layout, hipStream_t s)
 {
     const int64_t bpr = K / kBlock;
     const int64_t total = rows * bpr;
@@ -250,8 +432,8 @@ int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, con
         // grid.y is limited to 65535: fold the excess row groups into extra launches
         for (int64_t y0 = 0; y0 < gy; y0 += 65535) {
             const int64_t ny = gy - y0 < 65535 ? gy - y0 : 65535;
-            quantize_ktile_kernel<<<dim3((unsigned)((ksteps + 15) / 16), (unsigned)ny), dim3(kThreads), 0, s>>>(
-                x, rows, y0 * 16, (int)ksteps, ldx, alpha, codes, scales);
+            quantize_ktile_kernel<Src><<<dim3((unsigned)((ksteps + 15) / 16), (unsigned)ny), dim3(kThreads), 0, s>>>(
+                src, rows, y0 * 16, (int)ksteps, alpha, codes, scales);
             int rc = note_launch(hipGetLastError());
             if (rc != MQ_OK) return rc;
         }
@@ -259,12 +441,45 @@ int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, con
     }
     const int64_t grid = (total + kThreads - 1) / kThreads;
     if (grid > 0x7FFFFFFF) return MQ_ERR_SHAPE;
-    if (ldx == K)
-        quantize_kernel<true><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, total, (int)bpr, ldx, alpha,
-                                                                             codes, scales);
+    quantize_kernel<Src><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(src, total, (int)bpr, alpha, codes, scales);
+    return note_launch(hipGetLastError());
+}
+
+}  // namespace
+
+int launch_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const float *alpha,
+                    uint8_t *codes, uint8_t *scales, int layout, hipStream_t s)
+{
+    return launch_quantize_from(PlainSrc{x, ldx}, rows, K, alpha, codes, scales, layout, s);
+}
+
+int launch_quantize_silu_mul(const uint16_t *gate_up, int64_t rows, int64_t K, int64_t ld, const float *alpha,
+                             uint8_t *codes, uint8_t *scales, int layout, uint16_t *p, int64_t ldp, hipStream_t s)
+{
+    return launch_quantize_from(SiluMulSrc{gate_up, ld, K, p, ldp}, rows, K, alpha, codes, scales, layout, s);
+}
+
+int launch_quantize_rmsnorm(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, const uint16_t *w, float eps,
+                            const float *alpha, uint8_t *codes, uint8_t *scales, int layout, uint16_t *y,
+                            int64_t ldy, hipStream_t s)
+{
+    if (rows == 0) return MQ_OK;
+    const int64_t groups = (rows + 15) / 16;
+    if (groups > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    const int ksteps = (int)(K / 64);
+    const float inv_k = 1.0f / (float)K;
+    const dim3 grid((unsigned)groups), block(kRmsThreads);
+    const bool kt = layout == MQ_LAYOUT_KTILE;
+#define MQ_RMS(NC_)                                                                                              \
+    (kt ? rmsnorm_quantize_kernel<NC_, true><<<grid, block, 0, s>>>(x, rows, ksteps, ldx, w, eps, inv_k, alpha,  \
+                                                                    codes, scales, y, ldy)                      \
+        : rmsnorm_quantize_kernel<NC_, false><<<grid, block, 0, s>>>(x, rows, ksteps, ldx, w, eps, inv_k, alpha, \
+                                                                     codes, scales, y, ldy))
+    if (ksteps <= 64)
+        MQ_RMS(4);  // K <= 4096: the row stays in registers (32 per lane)
     else
-        quantize_kernel<false><<<dim3((unsigned)grid), dim3(kThreads), 0, s>>>(x, total, (int)bpr, ldx, alpha,
-                                                                              codes, scales);
+        MQ_RMS(0);  // (8 chunks in registers spill at 1024 threads per workgroup: measured 2x slower)
+#undef MQ_RMS
     return note_launch(hipGetLastError());
 }
 

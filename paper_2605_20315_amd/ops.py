@@ -63,6 +63,54 @@ def nvfp4_quantize(x_bf16: torch.Tensor, alpha: torch.Tensor, codes: torch.Tenso
     return codes, scales
 
 
+def _quant_outputs(rows: int, K: int, device, codes, scales, want_bf16: bool):
+    if codes is None:
+        codes = torch.empty((rows, K // 2), dtype=torch.uint8, device=device)
+    if scales is None:
+        scales = torch.empty((rows, K // BLOCK), dtype=torch.uint8, device=device)
+    assert codes.is_contiguous() and scales.is_contiguous()
+    dbg = torch.empty((rows, K), dtype=torch.bfloat16, device=device) if want_bf16 else None
+    return codes, scales, dbg
+
+
+def nvfp4_quantize_silu_mul(gate_up_bf16: torch.Tensor, alpha: torch.Tensor, codes: torch.Tensor | None = None,
+                            scales: torch.Tensor | None = None, layout: int = MQ_LAYOUT_LINEAR,
+                            return_bf16: bool = False):
+    """NVFP4 of silu(gate) * up for gate_up = [gate | up] of shape [rows, 2K] (fused producer).
+    Returns (codes, scales), plus the BF16 tensor that was quantized when return_bf16 is set."""
+    _need_gpu(gate_up_bf16, alpha)
+    assert gate_up_bf16.dtype == torch.bfloat16 and alpha.dtype == torch.float32
+    rows, k2, ld = _rows_k_ld(gate_up_bf16)
+    if k2 % (2 * BLOCK):
+        _lib.check(2, "nvfp4_quantize_silu_mul")
+    K = k2 // 2
+    codes, scales, p = _quant_outputs(rows, K, gate_up_bf16.device, codes, scales, return_bf16)
+    rc = _lib.load().nvfp4_quantize_silu_mul(gate_up_bf16.data_ptr(), rows, K, ld, alpha.data_ptr(),
+                                             codes.data_ptr(), scales.data_ptr(), layout,
+                                             p.data_ptr() if p is not None else None, K, _stream())
+    _lib.check(rc, "nvfp4_quantize_silu_mul")
+    return (codes, scales, p) if return_bf16 else (codes, scales)
+
+
+def nvfp4_quantize_rmsnorm(x_bf16: torch.Tensor, w_bf16: torch.Tensor, eps: float, alpha: torch.Tensor,
+                           codes: torch.Tensor | None = None, scales: torch.Tensor | None = None,
+                           layout: int = MQ_LAYOUT_LINEAR, return_bf16: bool = False):
+    """NVFP4 of x / sqrt(mean(x^2) + eps) * w per row (fused producer).
+    Returns (codes, scales), plus the BF16 tensor that was quantized when return_bf16 is set."""
+    _need_gpu(x_bf16, w_bf16, alpha)
+    assert x_bf16.dtype == torch.bfloat16 and w_bf16.dtype == torch.bfloat16 and alpha.dtype == torch.float32
+    rows, K, ld = _rows_k_ld(x_bf16)
+    assert w_bf16.shape == (K,) and w_bf16.is_contiguous()
+    if K % 64:
+        _lib.check(2, "nvfp4_quantize_rmsnorm")
+    codes, scales, y = _quant_outputs(rows, K, x_bf16.device, codes, scales, return_bf16)
+    rc = _lib.load().nvfp4_quantize_rmsnorm(x_bf16.data_ptr(), rows, K, ld, w_bf16.data_ptr(), float(eps),
+                                            alpha.data_ptr(), codes.data_ptr(), scales.data_ptr(), layout,
+                                            y.data_ptr() if y is not None else None, K, _stream())
+    _lib.check(rc, "nvfp4_quantize_rmsnorm")
+    return (codes, scales, y) if return_bf16 else (codes, scales)
+
+
 def nvfp4_relayout(codes: torch.Tensor, scales: torch.Tensor, from_layout: int, to_layout: int):
     """Copy an NVFP4 tensor into the other byte order (offline weight pre-pack).  Returns (codes, scales)."""
     _need_gpu(codes, scales)

@@ -54,6 +54,17 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.nvfp4_quantize(None, -1, 64, 64, None, None, None, 0, None) == 2
     assert lib.nvfp4_quantize(None, 4, 48, 48, None, None, None, 1, None) == 2      # KTILE needs K % 64
     assert lib.nvfp4_quantize(None, 4, 64, 64, None, None, None, 2, None) == 4      # unknown layout
+    # producer-fused quantizers
+    f = ctypes.c_float
+    assert lib.nvfp4_quantize_silu_mul(None, 4, 24, 48, None, None, None, 0, None, 0, None) == 2   # K % 16
+    assert lib.nvfp4_quantize_silu_mul(None, 4, 64, 100, None, None, None, 0, None, 0, None) == 2  # ld < 2K
+    assert lib.nvfp4_quantize_silu_mul(None, 4, 64, 128, None, None, None, 0, None, 0, None) == 1  # NULL
+    assert lib.nvfp4_quantize_silu_mul(None, 0, 64, 128, None, None, None, 1, None, 0, None) == 0  # empty
+    assert lib.nvfp4_quantize_silu_mul(None, 4, 64, 128, None, None, None, 7, None, 0, None) == 4
+    assert lib.nvfp4_quantize_rmsnorm(None, 4, 48, 48, None, f(1e-6), None, None, None, 0, None, 0, None) == 2
+    assert lib.nvfp4_quantize_rmsnorm(None, 0, 64, 64, None, f(-1.0), None, None, None, 0, None, 0, None) == 4
+    assert lib.nvfp4_quantize_rmsnorm(None, 0, 64, 64, None, f(1e-6), None, None, None, 0, None, 0, None) == 0
+    assert lib.nvfp4_quantize_rmsnorm(None, 4, 64, 64, None, f(1e-6), None, None, None, 0, None, 0, None) == 1
     assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 40, None, 8, 0, 0, None) == 2
     assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 3, 0, None) == 4
     assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 5, None) == 4
