@@ -232,7 +232,36 @@ def main() -> int:
             "rmsnorm_quantize": {"shape": [M, Kh], "fused_ms": round(t_f2, 4), "producer_then_quantize_ms": round(t_u2, 4),
                                  "fused_gbs": round(QUANT_BYTES_PER_ELT * M * Kh / (t_f2 * 1e-3) * 1e-9, 1)},
         }
-        del gu, xh, cd, sd, ch, sh
+        # the MLP half of a decoder block as a dependent chain (each step consumes the previous
+        # one's output): RMSNorm -> gate_up -> SiLU*up -> down, NVFP4 with fused quantizers against
+        # BF16 with the same in-repo GEMM; tensor-level scales calibrated once, untimed
+        by_name = {L["layer"].name: L for L in layers}
+        Lg, Ld = by_name["gate_up"], by_name["down"]
+        yg = torch.empty((M, 2 * Kd), dtype=torch.bfloat16, device="cuda")
+        yo = torch.empty((M, Kh), dtype=torch.bfloat16, device="cuda")
+        hn = torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6)
+        a_n = mq.nvfp4_global_scale(hn)
+        mq.bf16_gemm(hn, Lg["w"], mq.MQ_OUT_BF16, yg)
+        a_p = mq.nvfp4_global_scale(torch.nn.functional.silu(yg[:, :Kd]) * yg[:, Kd:])
+        del hn
+
+        def mlp_nvfp4():
+            mq.nvfp4_quantize_rmsnorm(xh, gw, 1e-6, a_n, ch, sh, LAYOUT)
+            mq.nvfp4_gemm(ch, sh, a_n, Lg["wc"], Lg["ws"], Lg["aw"], mq.MQ_OUT_BF16, yg, LAYOUT)
+            mq.nvfp4_quantize_silu_mul(yg, a_p, cd, sd, LAYOUT)
+            mq.nvfp4_gemm(cd, sd, a_p, Ld["wc"], Ld["ws"], Ld["aw"], mq.MQ_OUT_BF16, yo, LAYOUT)
+
+        def mlp_bf16():
+            h = torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6)
+            mq.bf16_gemm(h, Lg["w"], mq.MQ_OUT_BF16, yg)
+            pm = torch.nn.functional.silu(yg[:, :Kd]) * yg[:, Kd:]
+            mq.bf16_gemm(pm, Ld["w"], mq.MQ_OUT_BF16, yo)
+        t_m4, t_m16 = timed(mlp_nvfp4, 10), timed(mlp_bf16, 10)
+        mlp_flop = wl.layer_flops(M, Lg["layer"]) + wl.layer_flops(M, Ld["layer"])
+        fused["mlp_block_chain"] = {"nvfp4_ms": round(t_m4, 4), "bf16_ms": round(t_m16, 4),
+                                    "nvfp4_tflops": round(mlp_flop / (t_m4 * 1e-3) * 1e-12, 1),
+                                    "x_vs_bf16": round(t_m16 / t_m4, 3)}
+        del gu, xh, cd, sd, ch, sh, yg, yo
         torch.cuda.empty_cache()
 
     # ---- second workload: the paper's sweep axis (Section 4.4, Fig. 3: prefill speed-up over BF16
