@@ -24,6 +24,12 @@ def _cases():
         K = int(rng.integers(1, 40)) * 16
         out.append((M, N, K))
     out += [(4100, 4120, 64), (4352, 4352, 128), (3, 8, 16), (64, 8, 128), (65, 16, 128)]
+    # large enough for the register-direct kernels (whole tiles and split K), every output checked
+    for _ in range(6):
+        M = int(rng.integers(1400, 3200))
+        N = int(rng.integers(256, 520)) * 8
+        K = int(rng.integers(1, 9)) * 64
+        out.append((M, N, K))
     return out
 
 
