@@ -675,17 +675,19 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
 
 // ---- BF16, direct global-to-LDS loads ----------------------------------------------------------
 
-// 256x256x64 tile, four waves of 128x128 (one per SIMD), same LDS layout, phases and barrier as
-// gemm_bf16_pipelined, but the tiles never pass through registers: every wave issues 16
-// global_load_lds_dwordx4 per K step (1 KB each: 8 rows of one operand tile), which write LDS at
+// 256x256x64 tile with four waves of 128x128 (one per SIMD), or 256x128x64 with four waves of
+// 128x64; same LDS layout, phases and barrier as gemm_bf16_pipelined, but the tiles never pass
+// through registers: every wave issues 16 (12) global_load_lds_dwordx4 per K step (1 KB each:
+// 8 rows of one operand tile), which write LDS at
 // M0 + 16 * lane.  The bank swizzle is applied on the global side: the lane that fills chunk c' of
 // row r fetches chunk c' ^ key(r).  The loads are written in inline assembly because the compiler
 // orders every LDS read behind all outstanding LDS-writing loads (s_waitcnt vmcnt(0) right after
 // the load), which serialises the pipeline; here the only wait is the one before the barrier.
-template <bool OUT_BF16>
+template <class C, bool OUT_BF16>
 __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, int tiles_n)
 {
-    using C = PCfg<256, 256, 2, 2>;
+    static_assert(C::THREADS == 256, "four waves");
+    constexpr int GA = C::BM / 32, GB = C::BN / 32, NL = GA + GB;  // 8-row groups per wave and operand
     extern __shared__ uint4 lds[];
     char *const L = reinterpret_cast<char *>(lds);
     int tm, tn;
@@ -693,16 +695,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
     const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm0 = (wave >> 1) * C::WM, wn0 = (wave & 1) * C::WN;
+    const int wm0 = (wave / C::WAVES_N) * C::WM, wn0 = (wave % C::WAVES_N) * C::WN;
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = (int)(g.K / BK);
 
-    // group u of this wave: rows 8 * (wave * 8 + u) .. + 7 of the A tile (u < 8) or the B tile
-    uint32_t vo[16];
+    // load u of this wave: rows 8 * (wave * GA + u) .. + 7 of the A tile (u < GA), else of the B tile
+    uint32_t vo[NL];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const bool isA = u < 8;
-        const int r = 8 * (wave * 8 + (u & 7)) + (lane >> 3);
+    for (int u = 0; u < NL; ++u) {
+        const bool isA = u < GA;
+        const int r = 8 * (isA ? wave * GA + u : wave * GB + (u - GA)) + (lane >> 3);
         int64_t grow = (isA ? m0 : n0) + r;
         const int64_t total = isA ? g.M : g.N;
         grow = grow < total ? grow : total - 1;
@@ -710,11 +712,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
     }
     // LDS byte address of the dynamic segment
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)L;
-    // load u of tile t: one of this wave's 16 row groups (8 of A, 8 of B) into LDS stage `stage`
+    // load u of tile t into LDS stage `stage`
     auto load_group = [&](int t, int stage, int u) {
         t = t < KT ? t : KT - 1;
-        const char *base = static_cast<const char *>(u < 8 ? g.a : g.b) + (int64_t)t * (BK * 2);
-        const uint32_t dst = lds0 + (u < 8 ? 0 : C::B_BASE) + stage * C::A_STAGE + (wave * 8 + (u & 7)) * 1024;
+        const bool isA = u < GA;
+        const char *base = static_cast<const char *>(isA ? g.a : g.b) + (int64_t)t * (BK * 2);
+        const uint32_t dst = lds0 + (isA ? stage * C::A_STAGE + (wave * GA + u) * 1024
+                                         : C::B_BASE + stage * C::B_STAGE + (wave * GB + (u - GA)) * 1024);
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
                      : "s"(dst), "v"(vo[u]), "s"(base)
@@ -722,7 +726,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
     };
     auto load_tile = [&](int t, int stage) {
 #pragma unroll
-        for (int u = 0; u < 16; ++u) load_group(t, stage, u);
+        for (int u = 0; u < NL; ++u) load_group(t, stage, u);
     };
 
     int fa[4], fb[4];
@@ -778,17 +782,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
         // and nobody reads stage cur any more: it receives tile kt+2
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        // phase 3, written out: one MFMA, one fragment read (while any remain), one tile load
+        // phase 3, written out: per MFMA one fragment read (while any remain) and its share of
+        // the tile loads
 #pragma unroll
-        for (int n = 0; n < 16; ++n) {
-            const int i = n >> 2, j = n & 3;
+        for (int n = 0; n < NMFMA; ++n) {
+            const int i = n / C::TN, j = n % C::TN;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 __builtin_bit_cast(bf16x8, fra[1][i]), __builtin_bit_cast(bf16x8, frb[1][j]), acc[i][j], 0, 0, 0);
-            if (n < 4)
+            if (n < C::TM)
                 fra[0][n] = *reinterpret_cast<const uint4 *>(L + fa[0] + n * 4096 + nxt * C::A_STAGE);
-            else if (n < 8)
-                frb[0][n - 4] = *reinterpret_cast<const uint4 *>(L + fb[0] + (n - 4) * 4096 + nxt * C::B_STAGE);
-            load_group(kt + 2, cur, n);
+            else if (n < C::TM + C::TN)
+                frb[0][n - C::TM] = *reinterpret_cast<const uint4 *>(L + fb[0] + (n - C::TM) * 4096 + nxt * C::B_STAGE);
+#pragma unroll
+            for (int u = n * NL / NMFMA; u < (n + 1) * NL / NMFMA; ++u) load_group(kt + 2, cur, u);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -1106,7 +1112,7 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    using Mid = PCfg<256, 128, 2, 2>;   // BF16 only: 4 waves of 128x64, for one to two rounds of 256x256 tiles
+    using Mid = PCfg<256, 128, 2, 2>;   // BF16 only: 4 waves of 128x64
     using Small = PCfg<128, 128, 2, 2>;
     static std::atomic<bool> cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
@@ -1126,14 +1132,18 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         return launch_tiles(gemm_fp4_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
                             cfg_small);
     } else {
-        // 256x256 tiles once they fill the 256 CUs at least twice; smaller tiles below that.
+        // Same choice by rounds of workgroups as above: 256x256 tiles, or 256x128 tiles (half the
+        // work per workgroup, somewhat less efficient) when they waste less of the last round;
+        // 128x128 register-staged tiles for small problems.
+        int cus = 0;
+        if (int rc = compute_units(cus)) return rc;
+        const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus;
         using D = PCfg<256, 256, 2, 2>;
         static std::atomic<bool> cfg_d{false};
-        if (big_tiles >= 512)
-            return launch_tiles(gemm_bf16_d2l<OUT_BF16>, D::LDS_BYTES, 256, 256, D::THREADS, g, s, cfg_d);
-        if (mid_tiles >= 256)
-            return launch_tiles(gemm_bf16_pipelined<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s,
-                                cfg_mid);
+        if (2 * mid_tiles >= cus && 100 * r1 > 58 * r2)
+            return launch_tiles(gemm_bf16_d2l<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s, cfg_mid);
+        if (2 * mid_tiles >= cus)
+            return launch_tiles(gemm_bf16_d2l<D, OUT_BF16>, D::LDS_BYTES, 256, 256, D::THREADS, g, s, cfg_d);
         return launch_tiles(gemm_bf16_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
                             cfg_small);
     }
