@@ -39,6 +39,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--no-sweep", action="store_true", help="skip the tokens-per-batch sweep (second workload)")
+    ap.add_argument("--no-fused", action="store_true", help="skip the producer-fused quantizers and the MLP chain")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -202,7 +203,7 @@ def main() -> int:
     # ---- producer-fused quantizers (the quantizer fused with its neighbour, Section 3.3): the two
     # activations of a decoder block that are quantized, against producer (torch) + nvfp4_quantize ----
     fused = None
-    if args.config == 2:
+    if args.config == 2 and not args.no_fused:
         def timed(fn, reps=20):
             for _ in range(3):
                 fn()
