@@ -317,3 +317,30 @@ def test_gemm_errors_and_empty():
     assert lib.bf16_gemm(p(x), 8, p(x), 8, 4, 4, 12, p(y), 8, 0, st) == 2
     assert lib.bf16_gemm(p(x), 8, p(x), 8, 4, 4, 8, p(y), 8, 0, st) == 0
     torch.cuda.synchronize()
+
+
+def test_calls_follow_the_callers_stream():
+    """Every entry point enqueues on the stream it is given: a chain issued on a side stream while
+    the default stream is busy gives the same bytes as the same chain on the default stream."""
+    rng = np.random.default_rng(77)
+    M, K, N = 2048, 1024, 4096
+    x = dev_bf16(wl.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32)))
+    w = dev_bf16(wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32)))
+    aw = mq.nvfp4_global_scale(w)
+    wc, ws = mq.nvfp4_quantize(w, aw, layout=mq.MQ_LAYOUT_KTILE)
+
+    def chain():
+        ax = mq.nvfp4_global_scale(x)
+        xc, xs = mq.nvfp4_quantize(x, ax, layout=mq.MQ_LAYOUT_KTILE)
+        return mq.nvfp4_gemm(xc, xs, ax, wc, ws, aw, mq.MQ_OUT_BF16, layout=mq.MQ_LAYOUT_KTILE), mq.bf16_gemm(x, w)
+    ref4, ref16 = chain()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()            # default priority
+    big = torch.empty((8192, 8192), dtype=torch.bfloat16, device="cuda")
+    for _ in range(4):
+        big.normal_()                     # keeps the default stream busy
+    with torch.cuda.stream(side):
+        y4, y16 = chain()
+    side.synchronize()
+    assert torch.equal(y4, ref4) and torch.equal(y16, ref16)
+    torch.cuda.synchronize()
