@@ -344,3 +344,37 @@ def test_calls_follow_the_callers_stream():
     side.synchronize()
     assert torch.equal(y4, ref4) and torch.equal(y16, ref16)
     torch.cuda.synchronize()
+
+
+def test_chain_replays_from_a_hip_graph():
+    """The entry points allocate nothing and never synchronise, so a dynamic-alpha NVFP4 linear
+    (amax -> quantize -> GEMM) can be captured once and replayed on new inputs."""
+    rng = np.random.default_rng(78)
+    M, K, N = 2048, 1024, 4096
+    mk = lambda: dev_bf16(wl.f32_to_bf16_bits((rng.standard_normal((M, K)) * rng.uniform(0.5, 4.0)).astype(np.float32)))
+    w = dev_bf16(wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32)))
+    aw = mq.nvfp4_global_scale(w)
+    wc, ws = mq.nvfp4_quantize(w, aw, layout=mq.MQ_LAYOUT_KTILE)
+    x = mk()
+    ax = torch.empty(1, dtype=torch.float32, device="cuda")
+    xc = torch.empty((M, K // 2), dtype=torch.uint8, device="cuda")
+    xs = torch.empty((M, K // 16), dtype=torch.uint8, device="cuda")
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+
+    def chain():
+        mq.nvfp4_global_scale(x, ax)
+        mq.nvfp4_quantize(x, ax, xc, xs, mq.MQ_LAYOUT_KTILE)
+        mq.nvfp4_gemm(xc, xs, ax, wc, ws, aw, mq.MQ_OUT_BF16, y, mq.MQ_LAYOUT_KTILE)
+    chain()                                # eager warm-up: one-time kernel attributes are set here
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for _ in range(3):
+        x.copy_(mk())
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        chain()                            # eager, same input
+        torch.cuda.synchronize()
+        assert torch.equal(got, y)
