@@ -16,8 +16,9 @@
 //   gemm_fp4_direct     NVFP4 problems that fill at least half of the chip.  Four waves of
 //                       128x128 per workgroup, persistent workgroups, no LDS and no barriers in
 //                       the K loop: each wave loads its own operand rows in MFMA order and
-//                       expands them in registers (described at the kernel).  Either a 256x256
-//                       tile, or a 256x128 tile with K split over wave pairs.
+//                       expands them in registers (described at the kernel).  A 256x256 tile,
+//                       a 256x128 tile with K split over wave pairs, or a 128x128 tile with K
+//                       split over all four waves.
 //   gemm_fp4_pipelined  small NVFP4 problems (128x128 tiles): operands are expanded once per
 //                       workgroup while being staged into LDS.
 //   gemm_bf16_d2l       the BF16 baseline on large problems: 256x256 tile, four waves of 128x128,
@@ -361,24 +362,30 @@ struct RawTile {
 // SPLIT = 2 (problems that fill the chip only with finer tiles): the workgroup tile is 256x128,
 // its four waves are two 128x128 wave tiles times two halves of K; after the K loop each wave
 // hands the half of its accumulators that its partner will store to the partner through LDS.
+// SPLIT = 4: the workgroup tile is one 128x128 wave tile, its four waves take a quarter of K
+// each, and two such exchanges leave every wave with 32 fully summed rows to store.
 template <bool OUT_BF16, int SPLIT>
 __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, int tiles_n)
 {
     using C = PCfg<256, 256, 2, 2>;  // wave-level constants: 128x128 wave tile, 4x4 MFMA tiles
-    constexpr int BM = 256, BN = SPLIT == 1 ? 256 : 128;
+    static_assert(SPLIT == 1 || SPLIT == 2 || SPLIT == 4, "K is split over 1, 2 or 4 waves");
+    constexpr int BM = SPLIT == 4 ? 128 : 256, BN = SPLIT == 1 ? 256 : 128;
     constexpr int NSETS = 2;  // register sets of prefetched codes (3 measured no faster)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the K range depends on it
-    const int wm0 = SPLIT == 1 ? (wave >> 1) * 128 : (wave & 1) * 128, wn0 = SPLIT == 1 ? (wave & 1) * 128 : 0;
-    const int khalf = SPLIT == 1 ? 0 : wave >> 1;
-    // SPLIT = 2: the wave of the second K half holds its 32-row A tiles in the order 2,3,0,1, so
-    // that both waves of a pair keep accumulator rows 0..1 and send rows 2..3 (no divergent code)
-    const int aswap = khalf << 1;
+    const int wm0 = SPLIT == 1 ? (wave >> 1) * 128 : SPLIT == 2 ? (wave & 1) * 128 : 0;
+    const int wn0 = SPLIT == 1 ? (wave & 1) * 128 : 0;
+    const int kpart = SPLIT == 1 ? 0 : SPLIT == 2 ? wave >> 1 : wave;  // which part of K this wave sums
+    // SPLIT > 1: a wave holds its 32-row A tiles in the order i ^ aswap.  The tiles it will store
+    // then sit in accumulator rows 0.. and the ones it hands to its partner(s) behind them, the
+    // same in every wave (no divergent code): SPLIT = 2 keeps rows 0..1; SPLIT = 4 sends rows
+    // 2..3 to wave w^2 first, then row 1 to wave w^1, and keeps row 0 = output tile w.
+    const int aswap = SPLIT == 2 ? kpart << 1 : kpart;
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = (int)(g.K / BK);
-    // this wave's K steps [k0, k1); the first half is a whole number of NSETS groups
-    const int KH = SPLIT == 1 ? KT : ((KT + 1) / 2 + NSETS - 1) / NSETS * NSETS;
-    const int k0 = khalf * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
+    // this wave's K steps [k0, k1); every part but the last is a whole number of NSETS groups
+    const int KH = SPLIT == 1 ? KT : ((KT + SPLIT - 1) / SPLIT + NSETS - 1) / NSETS * NSETS;
+    const int k0 = kpart * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
     const int total_tiles = tiles_m * tiles_n;
 
     // Buffer loads: per K step a uniform resource whose 64-bit base is the start of that K step
@@ -515,38 +522,45 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         if constexpr (SPLIT == 1) {
             epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
         } else {
-            // Waves w and w^2 hold the two K halves of the same 128x128 tile.  Each keeps its
-            // accumulator rows 0..1 (output rows 0..63 in the first-half wave, 64..127 in the
-            // other, see aswap), sends rows 2..3 to its partner through LDS and adds what it
-            // receives (a + b in both, so the result does not depend on which wave adds).
-            // 1 KB per (32x32 tile, register quad) and wave.
+            // Waves that hold different parts of K for the same 128x128 tile exchange through LDS:
+            // a wave sends the accumulator rows [first, first + count) to `partner` and adds what
+            // the partner sent to its rows [0, count) (a + b in both, so the result does not
+            // depend on which wave adds).  1 KB per (32x32 tile, register quad) and wave.
             extern __shared__ uint4 lds[];
             typedef float f32x4 __attribute__((ext_vector_type(4)));
             f32x4 *const X = reinterpret_cast<f32x4 *>(lds);
+            auto exchange = [&](auto firstc, auto countc, int partner) {
+                constexpr int first = decltype(firstc)::value, count = decltype(countc)::value;
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < count; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const f32x16 &t = acc[2 + i][j];
-                        X[((wave * 8 + i * 4 + j) * 4 + c) * 64 + lane] =
-                            f32x4{t[4 * c], t[4 * c + 1], t[4 * c + 2], t[4 * c + 3]};
-                    }
-            __syncthreads();
-            const int partner = wave ^ 2;
+                        for (int c = 0; c < 4; ++c) {
+                            const f32x16 &t = acc[first + i][j];
+                            X[((wave * 8 + i * 4 + j) * 4 + c) * 64 + lane] =
+                                f32x4{t[4 * c], t[4 * c + 1], t[4 * c + 2], t[4 * c + 3]};
+                        }
+                __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < count; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                    for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const f32x4 v = X[((partner * 8 + i * 4 + j) * 4 + c) * 64 + lane];
+                        for (int c = 0; c < 4; ++c) {
+                            const f32x4 v = X[((partner * 8 + i * 4 + j) * 4 + c) * 64 + lane];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * c + e] += v[e];
-                    }
-            __syncthreads();  // the next tile's sends must not overtake these reads
-            epilogue<C, OUT_BF16, 0, 2>(g, acc, scale, m0, n0, wm0 + khalf * 64, wn0, frow, fhalf);
+                            for (int e = 0; e < 4; ++e) acc[i][j][4 * c + e] += v[e];
+                        }
+                __syncthreads();  // the next sends must not overtake these reads
+            };
+            exchange(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{}, wave ^ 2);
+            if constexpr (SPLIT == 2) {
+                epilogue<C, OUT_BF16, 0, 2>(g, acc, scale, m0, n0, wm0 + kpart * 64, wn0, frow, fhalf);
+            } else {
+                exchange(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, wave ^ 1);
+                epilogue<C, OUT_BF16, 0, 1>(g, acc, scale, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
+            }
         }
         if (!more) break;
     }
@@ -1052,7 +1066,7 @@ inline int compute_units(int &n)
 }
 
 template <class Kern>
-int launch_persistent(Kern kern, int bn, size_t lds_bytes, const GemmArgs &g, hipStream_t s, int cus,
+int launch_persistent(Kern kern, int bm, int bn, size_t lds_bytes, const GemmArgs &g, hipStream_t s, int cus,
                       std::atomic<bool> &configured)
 {
     if (lds_bytes > 0 && !configured.load(std::memory_order_acquire)) {
@@ -1061,7 +1075,7 @@ int launch_persistent(Kern kern, int bn, size_t lds_bytes, const GemmArgs &g, hi
         if (e != hipSuccess) return note_launch(e);
         configured.store(true, std::memory_order_release);
     }
-    const int64_t tiles_m = (g.M + 255) / 256, tiles_n = (g.N + bn - 1) / bn;
+    const int64_t tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
     const int64_t grid = tiles_m * tiles_n < cus ? tiles_m * tiles_n : cus;
     kern<<<dim3((unsigned)grid), dim3(256), lds_bytes, s>>>(g, (int)tiles_m, (int)tiles_n);
@@ -1117,18 +1131,25 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     static std::atomic<bool> cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
-        // Register-direct kernel once 256x128 workgroups fill at least half of the chip: whole
-        // 256x256 tiles, or 256x128 tiles with K split over wave pairs when that wastes less of
-        // the last round (such a workgroup takes 0.55 of the time of a whole one, measured).
-        // Below that, 128x128 LDS-pipelined tiles.
+        // Register-direct kernel once its workgroups fill at least half of the chip.  Three
+        // workgroup shapes: 256x256 (whole K per wave), 256x128 with K split over wave pairs,
+        // 128x128 with K split over the four waves; the one whose rounds of workgroups cost least
+        // wins, a split workgroup being charged 55 / 34 percent of a whole one (measured on
+        // M = 512 .. 8192).  Below that, 128x128 LDS-pipelined tiles.
         int cus = 0;
         if (int rc = compute_units(cus)) return rc;
-        const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus;
-        static std::atomic<bool> cfg_d1{false}, cfg_d2{false};
-        if (2 * mid_tiles >= cus && 100 * r1 > 55 * r2)
-            return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 128, 128 * 1024, g, s, cus, cfg_d2);
-        if (2 * mid_tiles >= cus)
-            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 0, g, s, cus, cfg_d1);
+        const int64_t small_tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
+        const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus,
+                      r4 = (small_tiles + cus - 1) / cus;
+        static std::atomic<bool> cfg_d1{false}, cfg_d2{false}, cfg_d4{false};
+        if (2 * small_tiles >= cus) {
+            const int64_t c1 = 100 * r1, c2 = 55 * r2, c4 = 34 * r4;
+            if (2 * mid_tiles < cus || (c4 < c1 && c4 < c2))
+                return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus, cfg_d4);
+            if (c2 < c1)
+                return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus, cfg_d2);
+            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus, cfg_d1);
+        }
         return launch_tiles(gemm_fp4_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
                             cfg_small);
     } else {

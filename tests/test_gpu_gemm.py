@@ -113,9 +113,9 @@ def test_large_tile_path_with_ragged_edges(K):
         assert torch.equal(y32.to(torch.bfloat16), y16)
 
 
-@pytest.mark.parametrize("M,N", [(256 * 16, 256 * 32), (2048, 4096)])
+@pytest.mark.parametrize("M,N", [(256 * 16, 256 * 32), (2048, 4096), (1024, 4096)])
 def test_register_direct_k_positions_one_hot(M, N):
-    """Register-direct kernel, whole tiles and split K: an element at every k of a K step must
+    """Register-direct kernel, whole tiles and K split two and four ways: an element at every k of a K step must
     meet exactly its partner.  A is a tall stack of one-hot rows (row r has a 1.0 at k = r % K),
     so Y[r, n] = B_hat[n, r % K]."""
     K = 128
@@ -185,6 +185,28 @@ def test_operand_larger_than_2_gib():
         check_gemm_fp32(y[ridx].cpu().numpy(), ref, na, nb)
         del acd, asd, y
         torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("K", [64, 192, 448, 1280])
+def test_four_way_split_k_path_with_ragged_edges(K):
+    """256 workgroup tiles of 128x128 select the register-direct kernel with K split over its four
+    waves (one K step: three parts are empty; three and seven: parts of unequal length)."""
+    rng = np.random.default_rng(25 + K)
+    M, N = 1000, 4000
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    a = oracle.dequantize(ac, asc, 0.5)
+    b = oracle.dequantize(bc, bsc, 0.25)
+    rows = np.unique(np.concatenate([np.arange(0, M, 37), np.arange(M - 40, M), [31, 32, 33, 63, 64, 95, 96, 127, 128]]))
+    ref = oracle.gemm_f64(a[rows], b)
+    na, nb = oracle.row_norms(a[rows]), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        y32 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32, layout)
+        check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+        y16 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16, layout)
+        check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
+        assert torch.equal(y32.to(torch.bfloat16), y16)
 
 
 def test_extreme_scales_subnormal_and_saturated():
