@@ -274,7 +274,7 @@ def main() -> int:
         sweep = {}
         gen = torch.Generator(device="cuda")
         gen.manual_seed(1234)
-        for ms in (2048, 4096, 16384, 32768, 65536, 131072):
+        for ms in (512, 1024, 2048, 4096, 16384, 32768, 65536, 131072):
             t_q4 = t_b16 = 0.0
             for L in layers:
                 K, N = L["layer"].K, L["layer"].N
