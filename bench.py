@@ -10,7 +10,11 @@ timed region; tensor-level scales and weight quantization are computed once, unt
 Prints ONE JSON line.  `value` = 2*M*N*K summed over the four layers / step time, in TFLOP/s.
 Also measured: the dominant kernel's (NVFP4 GEMM) average launch duration with HIP events on
 the launch stream (-> roofline), the quantizer's bandwidth, the in-repo BF16 GEMM on the same
-shapes (-> speed-up), and the CPU oracle on a bounded sample (-> cpu_baseline).
+shapes (-> speed-up), and the CPU oracle on a bounded sample (-> cpu_baseline).  Further lines of
+the same JSON object, all outside the timed region: the vendor library's BF16 GEMM as context,
+the dynamic-alpha pipeline, decode-shape weight streaming, the producer-fused quantizers and
+the MLP block as a dependent chain, a tokens-per-batch sweep (512 .. 131072), and the rate an
+MFMA-only loop sustains on this machine.
 """
 from __future__ import annotations
 
