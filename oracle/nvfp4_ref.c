@@ -17,8 +17,9 @@
  * the OCP "FN" flavour (no infinities, largest finite 448) and the projection saturates.
  *
  * Parity pins live in tests/ (format enumeration, exact-rational brute force, hand-worked
- * blocks, round-trip identity, closed-form GEMMs).  NaN inputs are outside the contract:
- * "parity unpinned" for NaN only.
+ * blocks, round-trip identity, closed-form GEMMs; for the two activation producers near the
+ * end of this file: identities, invariants, closed forms and library routines).  NaN inputs
+ * are outside the contract: "parity unpinned" for NaN only.
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC nvfp4_ref.c -lm
  */
