@@ -697,6 +697,10 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
 // row r fetches chunk c' ^ key(r).  The loads are written in inline assembly because the compiler
 // orders every LDS read behind all outstanding LDS-writing loads (s_waitcnt vmcnt(0) right after
 // the load), which serialises the pipeline; here the only wait is the one before the barrier.
+// The loads of tile t+2 are issued one per two MFMAs: the first half in the phase behind the
+// barrier that frees their stage, the second half in the first phase of the next K step.  All
+// 16 in the one phase measured 3 to 8 % slower (the texture path is shared by the four waves and
+// the same instants see everybody's loads), in one burst 5 % slower again; three phases no better.
 template <class C, bool OUT_BF16>
 __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, int tiles_n)
 {
@@ -765,15 +769,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
         for (int j = 0; j < C::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    auto mfmas = [&](const uint4(&a)[C::TM], const uint4(&b)[C::TN]) {
-#pragma unroll
-        for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
-    };
-    constexpr int NMFMA = C::TM * C::TN, NREAD = C::TM + C::TN;
+    constexpr int NMFMA = C::TM * C::TN;
 
     load_tile(0, 0);
     load_tile(1, 1);
@@ -781,36 +777,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
     __syncthreads();
     read_frags(0, 0, fra[0], frb[0]);
 
-    auto kstep = [&](int kt, auto par) {
-        constexpr int cur = decltype(par)::value, nxt = cur ^ 1;
-        read_frags(cur, 1, fra[1], frb[1]);
-        mfmas(fra[0], frb[0]);
-        sched_phase<NMFMA, NREAD, 0, 0, 0>();
-        read_frags(cur, 2, fra[0], frb[0]);
-        mfmas(fra[1], frb[1]);
-        sched_phase<NMFMA, NREAD, 0, 0, 0>();
-        read_frags(cur, 3, fra[1], frb[1]);
-        mfmas(fra[0], frb[0]);
-        sched_phase<NMFMA, NREAD, 0, 0, 0>();
-        // tile kt+1 has landed in this wave's share of stage nxt; after the barrier in everyone's,
-        // and nobody reads stage cur any more: it receives tile kt+2
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        // phase 3, written out: per MFMA one fragment read (while any remain) and its share of
-        // the tile loads
+    // One phase: the MFMAs of one 16-wide K sub-step on fragments (ca, cb); meanwhile the
+    // fragments of sub-step ks of stage rs are read into (na, nb), one per MFMA while any remain,
+    // and loads [U0, U1) of tile t go to stage ls, spread evenly over the MFMAs.
+    auto phase = [&](const uint4(&ca)[C::TM], const uint4(&cb)[C::TN], uint4(&na)[C::TM], uint4(&nb)[C::TN], int ks,
+                     int rs, int t, int ls, auto u0c, auto u1c) {
+        constexpr int U0 = decltype(u0c)::value, U1 = decltype(u1c)::value;
 #pragma unroll
         for (int n = 0; n < NMFMA; ++n) {
             const int i = n / C::TN, j = n % C::TN;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, fra[1][i]), __builtin_bit_cast(bf16x8, frb[1][j]), acc[i][j], 0, 0, 0);
+                __builtin_bit_cast(bf16x8, ca[i]), __builtin_bit_cast(bf16x8, cb[j]), acc[i][j], 0, 0, 0);
             if (n < C::TM)
-                fra[0][n] = *reinterpret_cast<const uint4 *>(L + fa[0] + n * 4096 + nxt * C::A_STAGE);
+                na[n] = *reinterpret_cast<const uint4 *>(L + fa[ks] + n * 4096 + rs * C::A_STAGE);
             else if (n < C::TM + C::TN)
-                frb[0][n - C::TM] = *reinterpret_cast<const uint4 *>(L + fb[0] + (n - C::TM) * 4096 + nxt * C::B_STAGE);
+                nb[n - C::TM] = *reinterpret_cast<const uint4 *>(L + fb[ks] + (n - C::TM) * 4096 + rs * C::B_STAGE);
 #pragma unroll
-            for (int u = n * NL / NMFMA; u < (n + 1) * NL / NMFMA; ++u) load_group(kt + 2, cur, u);
+            for (int u = U0 + n * (U1 - U0) / NMFMA; u < U0 + (n + 1) * (U1 - U0) / NMFMA; ++u) load_group(t, ls, u);
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    using U_0 = std::integral_constant<int, 0>;
+    using U_H = std::integral_constant<int, NL / 2>;
+    using U_N = std::integral_constant<int, NL>;
+    auto kstep = [&](int kt, auto par) {
+        constexpr int cur = decltype(par)::value, nxt = cur ^ 1;
+        // second half of tile kt+1 (the first K step of a tile fetches it a second time: harmless)
+        phase(fra[0], frb[0], fra[1], frb[1], 1, cur, kt + 1, nxt, U_H{}, U_N{});
+        phase(fra[1], frb[1], fra[0], frb[0], 2, cur, 0, 0, U_N{}, U_N{});
+        phase(fra[0], frb[0], fra[1], frb[1], 3, cur, 0, 0, U_N{}, U_N{});
+        // tile kt+1 has landed in this wave's share of stage nxt; after the barrier in everyone's,
+        // and nobody reads stage cur any more: it receives tile kt+2
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        phase(fra[1], frb[1], fra[0], frb[0], 0, nxt, kt + 2, cur, U_0{}, U_H{});
     };
     int kt = 0;
     for (; kt + 1 < KT; kt += 2) {
