@@ -154,6 +154,27 @@ int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_a
                void *stream);
 
 /*
+ * The same product (Section 3.3) with a caller-owned workspace.  Prefill chunks of a few
+ * hundred tokens have fewer 128x128 output tiles than the GPU has compute units, and the time
+ * is then the time to stream the weights once; with a workspace the K dimension is cut into
+ * slabs across workgroups, each writes FP32 partial sums to the workspace, and a second kernel
+ * adds the slabs in ascending order, applies alpha_a * alpha_b and rounds.  Same arguments,
+ * requirements, tolerance and run-to-run bit-identity as nvfp4_gemm; the summation order (and
+ * so the last bits) may differ from nvfp4_gemm's where slabs are used.
+ * workspace: device memory, 16-byte aligned, workspace_bytes >= 0 bytes, or NULL with 0; its
+ * contents are undefined afterwards and it must not be used by other work on another stream
+ * until this call's kernels have finished.  mq_gemm_workspace_bytes(M, N, K) (host function, no
+ * GPU access) returns the size that lets the library choose freely (never more than 16 MiB; 0
+ * where slabs are never used: N % 4 != 0, K % 64 != 0, K < 1024, or at least 64 output tiles
+ * of 128x128); a smaller workspace is legal and only limits the number of slabs.
+ */
+int64_t mq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+                  const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev,
+                  int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout,
+                  void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
  * High-precision baseline (the BF16 path that decoding keeps and that the paper's prefill
  * speed-up is measured against): Y = X . W^T, X [M, K] and W [N, K] BF16 with row strides
  * ldx, ldw elements, FP32 accumulation, output as in nvfp4_gemm.

@@ -8,7 +8,9 @@ from .ops import (  # noqa: F401
     MixQuantError,
     bf16_gemm,
     mfma_probe,
+    mq_gemm_workspace_bytes,
     nvfp4_gemm,
+    nvfp4_gemm_ws,
     nvfp4_global_scale,
     nvfp4_linear,
     nvfp4_quantize,

@@ -126,11 +126,31 @@ static int check_out(const void *y, int64_t N, int64_t ldy, int out)
     return MQ_OK;
 }
 
+// gfx950 parts have at most 256 compute units; the launcher uses what the device reports and
+// at most one 128x128 FP32 tile per compute unit.
+static constexpr int kMaxComputeUnits = 256;
+
+int64_t mq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const int ks = gemm_fp4_ksplit(M, N, K, INT64_MAX, kMaxComputeUnits);
+    return ks >= 2 ? (int64_t)ks * M * N * 4 : 0;
+}
+
 int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
                const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
                int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *stream)
 {
-    if (M < 0 || N < 0 || K <= 0 || K % kBlock != 0) return MQ_ERR_SHAPE;
+    return nvfp4_gemm_ws(a_codes, a_scales, a_alpha_dev, b_codes, b_scales, b_alpha_dev, M, N, K, y, ldy, out,
+                         layout, nullptr, 0, stream);
+}
+
+int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+                  const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
+                  int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *workspace,
+                  int64_t workspace_bytes, void *stream)
+{
+    if (M < 0 || N < 0 || K <= 0 || K % kBlock != 0 || workspace_bytes < 0) return MQ_ERR_SHAPE;
     if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
     if (layout != MQ_LAYOUT_LINEAR && layout != MQ_LAYOUT_KTILE) return MQ_ERR_ARG;
     if (layout == MQ_LAYOUT_KTILE && K % 64 != 0) return MQ_ERR_SHAPE;
@@ -143,7 +163,11 @@ int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_a
         !aligned(b_alpha_dev, 4))
         return MQ_ERR_ALIGN;
     if (K % 64 == 0 && (!aligned(a_scales, 4) || !aligned(b_scales, 4))) return MQ_ERR_ALIGN;
+    if (workspace && !aligned(workspace, 16)) return MQ_ERR_ALIGN;
     GemmArgs g{};
+    g.ws = workspace_bytes > 0 ? static_cast<float *>(workspace) : nullptr;
+    g.ws_bytes = g.ws ? workspace_bytes : 0;
+    g.ksplit = 1;
     g.a = a_codes;
     g.b = b_codes;
     g.a_scales = a_scales;

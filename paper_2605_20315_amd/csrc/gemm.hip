@@ -13,30 +13,32 @@
 // applied once in the epilogue.
 //
 // Kernels in this file
-//   gemm_fp4_direct     NVFP4 problems that fill at least half of the chip.  Four waves of
-//                       128x128 per workgroup, persistent workgroups, no LDS and no barriers in
-//                       the K loop: each wave loads its own operand rows in MFMA order and
-//                       expands them in registers (described at the kernel).  A 256x256 tile,
-//                       a 256x128 tile with K split over wave pairs, or a 128x128 tile with K
-//                       split over all four waves.
-//   gemm_fp4_pipelined  small NVFP4 problems (128x128 tiles): operands are expanded once per
-//                       workgroup while being staged into LDS.
+//   gemm_fp4_direct     every NVFP4 problem with K % 64 == 0.  Four waves of 128x128 per
+//                       workgroup, persistent workgroups, no LDS and no barriers in the K loop:
+//                       each wave loads its own operand rows in MFMA order and expands them in
+//                       registers (described at the kernel).  A 256x256 tile, a 256x128 tile
+//                       with K split over wave pairs, or a 128x128 tile with K split over all
+//                       four waves and, for a few hundred tokens and with a workspace, also
+//                       over workgroups (splitk_reduce_kernel then adds the slabs).
 //   gemm_bf16_d2l       the BF16 baseline on large problems: 256x256 tile, four waves of 128x128,
 //                       tiles loaded from global memory straight into LDS.
-//   gemm_bf16_pipelined the BF16 baseline on smaller problems, same LDS pipeline as above.
+//   gemm_bf16_pipelined the BF16 baseline on smaller problems, same LDS pipeline, tiles staged
+//                       through registers.
 //   bf16_skinny_kernel  BF16 with M <= 64 (decode shapes), weight streaming.
 //   gemm_simple_kernel  any K % 16 == 0 / K % 8 == 0 that the tiled kernels do not take.
 //
-// The LDS pipeline (both *_pipelined kernels): block tile BM x BN x 64, two LDS stages, and the
+// The LDS pipeline (the BF16 kernels): block tile BM x BN x 64, two LDS stages, and the
 // latencies covered inside each wave:
 //   * a K step of 64 is four MFMA phases of 16; the fragments of phase p+1 are read from LDS
 //     into a second register set while the MFMAs of phase p run;
-//   * NVFP4: the packed codes of a tile are fetched from global memory three K steps ahead into
-//     one of three register sets, and expanded to FP16 and written to the free LDS stage one
-//     quarter per phase, between the MFMAs; BF16: tiles are fetched one K step ahead into
-//     registers and written to the free LDS stage over two phases;
+//   * tiles are fetched two K steps ahead straight into the free LDS stage (gemm_bf16_d2l), or
+//     one K step ahead into registers and written to the free stage over two phases
+//     (gemm_bf16_pipelined);
 //   * one barrier per K step, at the start of phase 3: before it every wave has finished writing
 //     tile t+1 and reading tile t; after it tile t's stage is free and receives tile t+2.
+// (An NVFP4 kernel of the same structure, operands expanded once per workgroup on their way
+// into LDS, measured 6 % slower than the register-direct kernel on large problems and 1.4-1.8x
+// slower on small ones, and is gone.)
 // LDS rows are 128 bytes with a bank swizzle (below); tiles are walked in an XCD-aware grouped
 // order.  Rows beyond M or N are clamped to the last valid row instead of being zero-filled:
 // they only feed outputs that the epilogue does not store.
@@ -64,13 +66,11 @@ struct PCfg {
     static constexpr int THREADS = 64 * WAVES_M * WAVES_N;
     static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // per-wave tile
     static constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
-    static constexpr int PA = BM * 2 / THREADS, PB = BN * 2 / THREADS, NP = PA + PB;  // NVFP4 staging parts
     static constexpr int LA = BM * 8 / THREADS, LB = BN * 8 / THREADS;                // BF16 direct loads
     // LDS map in bytes: A stage 0, A stage 1, B stage 0, B stage 1 (stage strides fit the
     // 16-bit immediate offset of the LDS instructions)
     static constexpr int A_STAGE = BM * 128, B_STAGE = BN * 128, B_BASE = 2 * A_STAGE;
     static constexpr size_t LDS_BYTES = 2ull * (A_STAGE + B_STAGE);
-    static_assert(NP >= 2 && NP <= 4, "a thread stages 2 to 4 half rows per tile");
     static_assert(TM >= 1 && TN >= 1 && LA >= 1 && LB >= 1, "tile too small for this wave grid");
 };
 
@@ -79,12 +79,15 @@ struct PCfg {
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Give each XCD a contiguous range of
 // logical tile ids, then walk tiles in groups of GROUP_M tile rows, column by column, so that
 // the tiles resident on one XCD at a time share A row-panels and B column-panels in its L2.
-__device__ __forceinline__ void tile_of(int wg, int tiles_m, int tiles_n, int &tm, int &tn)
+__device__ __forceinline__ int logical_id(int wg, int total)
 {
-    const int total = tiles_m * tiles_n;
     const int xcd = wg % NUM_XCD, idx = wg / NUM_XCD;
     const int per = total / NUM_XCD, rem = total % NUM_XCD;
-    const int t = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    return xcd * per + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ __forceinline__ void tile_of_logical(int t, int tiles_m, int tiles_n, int &tm, int &tn)
+{
     constexpr int GROUP_M = 8;
     const int group_size = GROUP_M * tiles_n;
     const int g = t / group_size;
@@ -93,6 +96,11 @@ __device__ __forceinline__ void tile_of(int wg, int tiles_m, int tiles_n, int &t
     const int in_g = t - g * group_size;
     tm = first_m + in_g % gm;
     tn = in_g / gm;
+}
+
+__device__ __forceinline__ void tile_of(int wg, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    tile_of_logical(logical_id(wg, tiles_m * tiles_n), tiles_m, tiles_n, tm, tn);
 }
 
 // Scheduling hint for one phase: per MFMA one LDS read (while any remain), a few VALU
@@ -153,193 +161,6 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, f32x16 (&acc)[C::TM]
         }
 }
 
-// ---- NVFP4 ----------------------------------------------------------------------------------
-
-struct Fp4Part {
-    uint4 c;       // 32 codes of this thread's half row
-    uint32_t sc;   // the row's four E4M3 scale bytes for this K step (both halves)
-};
-
-// 8 codes (one dword) times one block scale -> 8 FP16 values sigma*q (exact).  sigma2 holds
-// sigma*2^-8 twice: an E4M3 byte shifted left by 7 is that FP16 number, subnormal scales
-// included; the conversion supplies the missing 2^8 through its (exponent-only) scale operand.
-__device__ __forceinline__ uint4 expand8(uint32_t w, uint32_t sigma2)
-{
-    const f16x2 s = __builtin_bit_cast(f16x2, sigma2);
-    f16x2 h0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 0) * s;
-    f16x2 h1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 1) * s;
-    f16x2 h2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 2) * s;
-    f16x2 h3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 3) * s;
-    return make_uint4(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
-                      __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3));
-}
-
-template <class C, bool OUT_BF16>
-__global__ __launch_bounds__(C::THREADS) void gemm_fp4_pipelined(GemmArgs g, int tiles_m, int tiles_n)
-{
-    extern __shared__ uint4 lds[];
-    char *const L = reinterpret_cast<char *>(lds);
-    int tm, tn;
-    tile_of(blockIdx.x, tiles_m, tiles_n, tm, tn);
-    const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm0 = (wave / C::WAVES_N) * C::WM, wn0 = (wave % C::WAVES_N) * C::WN;
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int half = tid & 1;
-    const int KT = (int)(g.K / BK);
-
-    // Staging: part q of a tile is half a row (32 codes) of operand A (q < PA) or B.  Global
-    // addresses are a uniform base (advanced per K step) plus a 32-bit per-thread offset.
-    uint32_t vc[C::NP], vs[C::NP];  // byte offsets of this thread's codes / scale word
-    int wad[C::NP][4];              // LDS byte address (stage 0) of each of the 4 expanded chunks
-#pragma unroll
-    for (int q = 0; q < C::NP; ++q) {
-        const bool isA = q < C::PA;
-        // A wave stages 32 rows; its lane pairs take the even rows first, then the odd ones, so
-        // that the 8 lanes the LDS serves together on a 128-bit write (32 banks, 128 bytes per
-        // clock) hold rows with 4 different swizzle keys and hit 8 different bank groups.
-        const int idx = lane >> 1;
-        const int r = wave * 32 + (((idx & 15) << 1) | (idx >> 4)) + (isA ? q : q - C::PA) * (C::THREADS / 2);
-        const int64_t total = isA ? g.M : g.N, row0 = isA ? m0 : n0;
-        int64_t grow = row0 + r;
-        grow = grow < total ? grow : total - 1;
-        vc[q] = (uint32_t)(grow * (isA ? g.a_c_row : g.b_c_row) + half * 16);
-        vs[q] = (uint32_t)(grow * (isA ? g.a_s_row : g.b_s_row));
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            wad[q][j] = (isA ? 0 : C::B_BASE) + (r * 8 + ((half * 4 + j) ^ swz_key(r))) * 16;
-    }
-    Fp4Part st[3][C::NP];  // tile T waits in register set T % 3
-    auto load_tile = [&](int t, Fp4Part(&s)[C::NP]) {
-        t = t < KT ? t : KT - 1;
-        const uint8_t *ac = static_cast<const uint8_t *>(g.a) + (int64_t)t * g.a_c_step;
-        const uint8_t *bc = static_cast<const uint8_t *>(g.b) + (int64_t)t * g.b_c_step;
-        const uint8_t *as = g.a_scales + (int64_t)t * g.a_s_step;
-        const uint8_t *bs = g.b_scales + (int64_t)t * g.b_s_step;
-#pragma unroll
-        for (int q = 0; q < C::NP; ++q) {
-            s[q].c = *reinterpret_cast<const uint4 *>((q < C::PA ? ac : bc) + vc[q]);
-            s[q].sc = *reinterpret_cast<const uint32_t *>((q < C::PA ? as : bs) + vs[q]);
-        }
-    };
-    // Half a part: 16 codes of one scale block -> two 16-byte chunks of FP16 in LDS.
-    auto store_half = [&](int q, int h, Fp4Part p, int stage) {
-        // Pin the first use of the prefetched registers to this point of the program: without
-        // it the compiler sinks cheap consumers of the loads to the loop header, right behind
-        // the loads themselves, and the wait for them lands phases too early.
-        uint32_t c0 = h ? p.c.z : p.c.x, c1 = h ? p.c.w : p.c.y, sc = p.sc;
-        asm volatile("" : "+v"(c0), "+v"(c1), "+v"(sc));
-        const uint32_t byte = (sc >> (half * 16 + h * 8)) & 0xFFu;  // this block's E4M3 scale
-        const uint32_t b = byte << 7, s2 = b | (b << 16);           // sigma * 2^-8 as FP16, twice
-        const int so = stage * (q < C::PA ? C::A_STAGE : C::B_STAGE);
-        *reinterpret_cast<uint4 *>(L + wad[q][2 * h] + so) = expand8(c0, s2);
-        *reinterpret_cast<uint4 *>(L + wad[q][2 * h + 1] + so) = expand8(c1, s2);
-    };
-    // A tile's 2*NP half-parts are spread evenly over four rotating slots
-    // (slot 0: phase 3 of the K step before, slots 1..3: phases 0..2).
-    auto store_slot = [&](int slot, const Fp4Part(&s)[C::NP], int stage) {
-#pragma unroll
-        for (int u = 0; u < 2 * C::NP; ++u)
-            if (u * 4 / (2 * C::NP) == slot) store_half(u >> 1, u & 1, s[u >> 1], stage);
-    };
-
-    // fragment byte addresses (stage 0): one per phase; the 32-row tiles of a wave are 4096 bytes apart
-    int fa[4], fb[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        fa[ks] = ((wm0 + frow) * 8 + ((ks * 2 + fhalf) ^ swz_key(frow))) * 16;
-        fb[ks] = C::B_BASE + ((wn0 + frow) * 8 + ((ks * 2 + fhalf) ^ swz_key(frow))) * 16;
-    }
-    uint4 fra[2][C::TM], frb[2][C::TN];
-    auto read_frags = [&](int stage, int ks, uint4(&a)[C::TM], uint4(&b)[C::TN]) {
-#pragma unroll
-        for (int i = 0; i < C::TM; ++i)
-            a[i] = *reinterpret_cast<const uint4 *>(L + fa[ks] + i * 4096 + stage * C::A_STAGE);
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-            b[j] = *reinterpret_cast<const uint4 *>(L + fb[ks] + j * 4096 + stage * C::B_STAGE);
-    };
-
-    f32x16 acc[C::TM][C::TN];
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-    auto mfmas = [&](const uint4(&a)[C::TM], const uint4(&b)[C::TN]) {
-#pragma unroll
-        for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                    __builtin_bit_cast(f16x8, a[i]), __builtin_bit_cast(f16x8, b[j]), acc[i][j], 0, 0, 0);
-    };
-
-    constexpr int NMFMA = C::TM * C::TN, NREAD = C::TM + C::TN;
-    // every phase expands about NP/2 half-parts: some 11 VALU instructions and 2 LDS writes each
-    constexpr int N_W = (C::NP + 1) / 2 * 2 <= NMFMA ? (C::NP + 1) / 2 * 2 : NMFMA;
-    constexpr int N_V = (11 * C::NP + NMFMA - 1) / NMFMA;
-
-    // prologue
-    load_tile(0, st[0]);
-    load_tile(1, st[1]);
-    load_tile(2, st[2]);
-#pragma unroll
-    for (int slot = 0; slot < 4; ++slot) store_slot(slot, st[0], 0);
-    store_slot(0, st[1], 1);
-    load_tile(3, st[0]);
-    __syncthreads();
-    read_frags(0, 0, fra[0], frb[0]);
-
-    // one K step; R = kt % 6 fixes the LDS stage (kt % 2) and the register sets (kt % 3) at compile time
-    auto kstep = [&](int kt, auto rr) {
-        constexpr int R = decltype(rr)::value;
-        constexpr int cur = R % 2, nxt = cur ^ 1;
-        Fp4Part(&s_next)[C::NP] = st[(R + 1) % 3];  // tile kt+1, later refilled with tile kt+4
-        Fp4Part(&s_cur)[C::NP] = st[(R + 2) % 3];   // tile kt+2
-        // phase 0
-        read_frags(cur, 1, fra[1], frb[1]);
-        store_slot(1, s_next, nxt);
-        mfmas(fra[0], frb[0]);
-        sched_phase<NMFMA, NREAD, N_V, N_W, 0>();
-        // phase 1
-        read_frags(cur, 2, fra[0], frb[0]);
-        store_slot(2, s_next, nxt);
-        mfmas(fra[1], frb[1]);
-        sched_phase<NMFMA, NREAD, N_V, N_W, 0>();
-        // phase 2
-        read_frags(cur, 3, fra[1], frb[1]);
-        store_slot(3, s_next, nxt);
-        mfmas(fra[0], frb[0]);
-        sched_phase<NMFMA, NREAD, N_V, N_W, 0>();
-        // phase 3
-        __syncthreads();
-        read_frags(nxt, 0, fra[0], frb[0]);
-        store_slot(0, s_cur, cur);
-        load_tile(kt + 4, s_next);
-        mfmas(fra[1], frb[1]);
-        sched_phase<NMFMA, NREAD, N_V, N_W, 2 * C::NP>();
-    };
-    int kt = 0;
-    for (; kt + 5 < KT; kt += 6) {
-        kstep(kt, std::integral_constant<int, 0>{});
-        kstep(kt + 1, std::integral_constant<int, 1>{});
-        kstep(kt + 2, std::integral_constant<int, 2>{});
-        kstep(kt + 3, std::integral_constant<int, 3>{});
-        kstep(kt + 4, std::integral_constant<int, 4>{});
-        kstep(kt + 5, std::integral_constant<int, 5>{});
-    }
-    if (kt < KT) kstep(kt, std::integral_constant<int, 0>{});
-    if (kt + 1 < KT) kstep(kt + 1, std::integral_constant<int, 1>{});
-    if (kt + 2 < KT) kstep(kt + 2, std::integral_constant<int, 2>{});
-    if (kt + 3 < KT) kstep(kt + 3, std::integral_constant<int, 3>{});
-    if (kt + 4 < KT) kstep(kt + 4, std::integral_constant<int, 4>{});
-
-    const float scale = (*g.a_alpha) * (*g.b_alpha);
-    epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
-}
-
 // ---- NVFP4, register-direct ------------------------------------------------------------------
 
 // The same product without LDS and without barriers.  A wave owns a 128x128 output tile (four
@@ -364,9 +185,14 @@ struct RawTile {
 // hands the half of its accumulators that its partner will store to the partner through LDS.
 // SPLIT = 4: the workgroup tile is one 128x128 wave tile, its four waves take a quarter of K
 // each, and two such exchanges leave every wave with 32 fully summed rows to store.
-template <bool OUT_BF16, int SPLIT>
+// XSPLIT (with SPLIT = 4; problems with fewer 128x128 tiles than compute units, i.e. a few
+// hundred tokens): K is also cut into g.ksplit slabs across workgroups.  A work item is (slab,
+// tile); its workgroup writes the FP32 partial sums of the slab to g.ws[slab][M][N] (unscaled),
+// and splitk_reduce_kernel adds the slabs in ascending order, scales and rounds.
+template <bool OUT_BF16, int SPLIT, bool XSPLIT = false>
 __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, int tiles_n)
 {
+    static_assert(!XSPLIT || SPLIT == 4, "slabs of K across workgroups: only with the four-way split inside");
     using C = PCfg<256, 256, 2, 2>;  // wave-level constants: 128x128 wave tile, 4x4 MFMA tiles
     static_assert(SPLIT == 1 || SPLIT == 2 || SPLIT == 4, "K is split over 1, 2 or 4 waves");
     constexpr int BM = SPLIT == 4 ? 128 : 256, BN = SPLIT == 1 ? 256 : 128;
@@ -384,9 +210,26 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = (int)(g.K / BK);
     // this wave's K steps [k0, k1); every part but the last is a whole number of NSETS groups
-    const int KH = SPLIT == 1 ? KT : ((KT + SPLIT - 1) / SPLIT + NSETS - 1) / NSETS * NSETS;
-    const int k0 = kpart * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
-    const int total_tiles = tiles_m * tiles_n;
+    const int parts = SPLIT * (XSPLIT ? g.ksplit : 1);
+    const int KH = SPLIT == 1 ? KT : ((KT + parts - 1) / parts + NSETS - 1) / NSETS * NSETS;
+    int k0 = kpart * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
+    const int tiles = tiles_m * tiles_n;
+    const int total_tiles = XSPLIT ? tiles * g.ksplit : tiles;  // work items
+    int slab = 0;
+    // work item -> tile and, with XSPLIT, K slab (items of one slab are contiguous, so that the
+    // workgroups of an XCD share a slab of A)
+    auto item_of = [&](int item, int &tm, int &tn) {
+        if constexpr (XSPLIT) {
+            const int t = logical_id(item, total_tiles);
+            slab = t / tiles;
+            tile_of_logical(t - slab * tiles, tiles_m, tiles_n, tm, tn);
+            k0 = (slab * SPLIT + kpart) * KH;
+            k0 = k0 < KT ? k0 : KT;  // a wave past the end sums nothing
+            k1 = (k0 + KH < KT) ? k0 + KH : KT;
+        } else {
+            tile_of(item, tiles_m, tiles_n, tm, tn);
+        }
+    };
 
     // Buffer loads: per K step a uniform resource whose 64-bit base is the start of that K step
     // (scalar arithmetic only), plus the lane's row and half as a 32-bit vector offset.  Rows
@@ -489,7 +332,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     const float scale = (*g.a_alpha) * (*g.b_alpha);
     int tile = blockIdx.x;
     int tm, tn;
-    tile_of(tile, tiles_m, tiles_n, tm, tn);
+    item_of(tile, tm, tn);
     set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
     for (int u = 0; u < NSETS; ++u) load_tile(k0 + u, st[u]);
@@ -513,8 +356,9 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         }
         tile += gridDim.x;
         const bool more = tile < total_tiles;
+        const int done_slab = slab;
         if (more) {
-            tile_of(tile, tiles_m, tiles_n, tm, tn);
+            item_of(tile, tm, tn);
             set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
             for (int u = 0; u < NSETS; ++u) load_tile(k0 + u, st[u]);
@@ -559,10 +403,42 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
                 epilogue<C, OUT_BF16, 0, 2>(g, acc, scale, m0, n0, wm0 + kpart * 64, wn0, frow, fhalf);
             } else {
                 exchange(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, wave ^ 1);
-                epilogue<C, OUT_BF16, 0, 1>(g, acc, scale, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
+                if constexpr (XSPLIT) {
+                    GemmArgs part = g;  // the slab's [M, N] FP32 matrix of partial sums
+                    part.y = g.ws + (int64_t)done_slab * g.M * g.N;
+                    part.ldy = g.N;
+                    epilogue<C, false, 0, 1>(part, acc, 1.0f, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
+                } else {
+                    epilogue<C, OUT_BF16, 0, 1>(g, acc, scale, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
+                }
             }
         }
         if (!more) break;
+    }
+}
+
+// Second pass of the slab-split product: y[m][n] = round(scale * (ws[0][m][n] + ws[1][m][n] + ...)),
+// slabs added in ascending order.  One thread per four consecutive columns (N % 4 == 0 here).
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g)
+{
+    const int64_t quads_per_row = g.N / 4, total = g.M * quads_per_row;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int64_t m = i / quads_per_row, n = (i - m * quads_per_row) * 4;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 *p = reinterpret_cast<const f32x4 *>(g.ws + m * g.N + n);
+    const int64_t slab_quads = g.M * g.N / 4;
+    f32x4 sum = p[0];
+    for (int sl = 1; sl < g.ksplit; ++sl) sum += p[sl * slab_quads];
+    const float scale = (*g.a_alpha) * (*g.b_alpha);
+    sum *= scale;
+    if constexpr (OUT_BF16) {
+        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+        const bf16x4 o = {(__bf16)sum[0], (__bf16)sum[1], (__bf16)sum[2], (__bf16)sum[3]};
+        *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(g.y) + m * g.ldy + n) = o;
+    } else {
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.y) + m * g.ldy + n) = sum;
     }
 }
 
@@ -1067,7 +943,7 @@ inline int compute_units(int &n)
 
 template <class Kern>
 int launch_persistent(Kern kern, int bm, int bn, size_t lds_bytes, const GemmArgs &g, hipStream_t s, int cus,
-                      std::atomic<bool> &configured)
+                      std::atomic<bool> &configured, int items_per_tile = 1)
 {
     if (lds_bytes > 0 && !configured.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -1077,7 +953,9 @@ int launch_persistent(Kern kern, int bm, int bn, size_t lds_bytes, const GemmArg
     }
     const int64_t tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
-    const int64_t grid = tiles_m * tiles_n < cus ? tiles_m * tiles_n : cus;
+    const int64_t items = tiles_m * tiles_n * items_per_tile;
+    if (items > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    const int64_t grid = items < cus ? items : cus;
     kern<<<dim3((unsigned)grid), dim3(256), lds_bytes, s>>>(g, (int)tiles_m, (int)tiles_n);
     return note_launch(hipGetLastError());
 }
@@ -1127,15 +1005,14 @@ int launch_any(const GemmArgs &g, hipStream_t s)
     if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
     using Mid = PCfg<256, 128, 2, 2>;   // BF16 only: 4 waves of 128x64
-    using Small = PCfg<128, 128, 2, 2>;
+    using Small = PCfg<128, 128, 2, 2>;  // BF16 only: 4 waves of 64x64
     static std::atomic<bool> cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
-        // Register-direct kernel once its workgroups fill at least half of the chip.  Three
-        // workgroup shapes: 256x256 (whole K per wave), 256x128 with K split over wave pairs,
-        // 128x128 with K split over the four waves; the one whose rounds of workgroups cost least
-        // wins, a split workgroup being charged 55 / 34 percent of a whole one (measured on
-        // M = 512 .. 8192).  Below that, 128x128 LDS-pipelined tiles.
+        // Three workgroup shapes: 256x256 (whole K per wave), 256x128 with K split over wave
+        // pairs, 128x128 with K split over the four waves; once the 128x128 tiles fill at least
+        // half of the chip, the one whose rounds of workgroups cost least wins, a split workgroup
+        // being charged 55 / 34 percent of a whole one (measured on M = 512 .. 8192).
         int cus = 0;
         if (int rc = compute_units(cus)) return rc;
         const int64_t small_tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
@@ -1150,8 +1027,23 @@ int launch_any(const GemmArgs &g, hipStream_t s)
                 return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus, cfg_d2);
             return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus, cfg_d1);
         }
-        return launch_tiles(gemm_fp4_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
-                            cfg_small);
+        // Fewer 128x128 tiles than half the compute units (a few hundred tokens): the time is the
+        // weights' way from HBM, and only more workgroups pull harder.  With a workspace, K is cut
+        // into slabs across workgroups (one round of work items) and a second kernel adds the
+        // slabs; without one, the four-way split inside the workgroup is what there is.
+        const int ks = gemm_fp4_ksplit(g.M, g.N, g.K, g.ws ? g.ws_bytes : 0, cus);
+        if (ks >= 2) {
+            GemmArgs gs = g;
+            gs.ksplit = ks;
+            static std::atomic<bool> cfg_x4{false};
+            if (int rc = launch_persistent(gemm_fp4_direct<OUT_BF16, 4, true>, 128, 128, 128 * 1024, gs, s, cus, cfg_x4,
+                                           ks))
+                return rc;
+            const int64_t quads = g.M * (g.N / 4);
+            splitk_reduce_kernel<OUT_BF16><<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(gs);
+            return note_launch(hipGetLastError());
+        }
+        return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus, cfg_d4);
     } else {
         // Same choice by rounds of workgroups as above: 256x256 tiles, or 256x128 tiles (half the
         // work per workgroup, somewhat less efficient) when they waste less of the last round;
@@ -1171,6 +1063,27 @@ int launch_any(const GemmArgs &g, hipStream_t s)
 }
 
 }  // namespace
+
+int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
+{
+    if (M <= 0 || N <= 0 || K % BK != 0 || N % 4 != 0 || ws_bytes <= 0) return 1;
+    const int64_t small_tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    if (2 * small_tiles >= cus) return 1;  // enough tiles: no slabs
+    const int64_t kt = K / BK;
+    int64_t ks_max = cus / small_tiles;    // one round of work items
+    if (ks_max > kt / 8) ks_max = kt / 8;  // at least two K steps for each of a workgroup's four waves
+    const int64_t fit = ws_bytes / (M * N * 4);
+    if (ks_max > fit) ks_max = fit;
+    // Cost in ns: a wave's K steps (1.1 us each, measured) plus, with slabs, the second launch and
+    // the partial sums' way to the workspace and back (4 TB/s).
+    int64_t best = 1, best_cost = INT64_MAX;
+    for (int64_t ks = 1; ks <= ks_max; ++ks) {
+        const int64_t kh = ((kt + 4 * ks - 1) / (4 * ks) + 1) / 2 * 2;
+        const int64_t cost = kh * 1100 + (ks > 1 ? 3000 + ks * M * N * 8 / 4000 : 0);
+        if (cost < best_cost) best = ks, best_cost = cost;
+    }
+    return (int)best;
+}
 
 int launch_mfma_probe(float *out, int iters, int blocks, hipStream_t s)
 {

@@ -55,7 +55,14 @@ struct GemmArgs {
     void *y;
     int64_t ldy;
     int out;                  // mq_out
+    // optional workspace for partial sums (NVFP4, problems of a few 128x128 tiles): ws_bytes of
+    // device memory, 16-byte aligned, or NULL / 0.  ksplit is filled in by the launcher.
+    float *ws;
+    int64_t ws_bytes;
+    int ksplit;
 };
+// K slabs the NVFP4 launcher would cut a problem into (1: none), given this much workspace
+int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
 int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);
 int launch_gemm_bf16(const GemmArgs &g, hipStream_t s);
 int launch_mfma_probe(float *out, int iters, int blocks, hipStream_t s);

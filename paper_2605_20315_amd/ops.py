@@ -144,6 +144,37 @@ def nvfp4_gemm(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int 
     return y
 
 
+def mq_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    """Workspace size that lets nvfp4_gemm_ws choose its K slabs freely (0: it would use none)."""
+    return int(_lib.load().mq_gemm_workspace_bytes(M, N, K))
+
+
+def nvfp4_gemm_ws(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, workspace: torch.Tensor | None,
+                  out: int = MQ_OUT_BF16, y: torch.Tensor | None = None,
+                  layout: int = MQ_LAYOUT_LINEAR) -> torch.Tensor:
+    """nvfp4_gemm with a caller-owned workspace (any contiguous GPU tensor, or None) for the partial
+    sums of small-M problems."""
+    _need_gpu(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha)
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    assert b_codes.shape[1] * 2 == K and a_scales.shape == (M, K // BLOCK) and b_scales.shape == (N, K // BLOCK)
+    for t in (a_codes, a_scales, b_codes, b_scales):
+        assert t.dtype == torch.uint8 and t.is_contiguous()
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16 if out == MQ_OUT_BF16 else torch.float32,
+                        device=a_codes.device)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    ws_ptr, ws_bytes = 0, 0
+    if workspace is not None:
+        assert workspace.is_cuda and workspace.is_contiguous()
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    rc = _lib.load().nvfp4_gemm_ws(a_codes.data_ptr(), a_scales.data_ptr(), a_alpha.data_ptr(),
+                                   b_codes.data_ptr(), b_scales.data_ptr(), b_alpha.data_ptr(),
+                                   M, N, K, y.data_ptr(), ldy, out, layout, ws_ptr, ws_bytes, _stream())
+    _lib.check(rc, "nvfp4_gemm_ws")
+    return y
+
+
 def bf16_gemm(x_bf16: torch.Tensor, w_bf16: torch.Tensor, out: int = MQ_OUT_BF16,
               y: torch.Tensor | None = None) -> torch.Tensor:
     """Y = X . W^T with BF16 inputs and FP32 accumulation (the high-precision baseline)."""
@@ -164,11 +195,11 @@ def bf16_gemm(x_bf16: torch.Tensor, w_bf16: torch.Tensor, out: int = MQ_OUT_BF16
 
 def nvfp4_linear(x_bf16: torch.Tensor, alpha_x: torch.Tensor, w_codes, w_scales, alpha_w,
                  out: int = MQ_OUT_BF16, y: torch.Tensor | None = None, codes=None, scales=None,
-                 layout: int = MQ_LAYOUT_LINEAR):
+                 layout: int = MQ_LAYOUT_LINEAR, workspace: torch.Tensor | None = None):
     """One prefill linear layer: quantize the activations, then the block-scaled GEMM (two library
     calls).  `layout` is the byte order of the weight arrays and of the activation arrays produced here."""
     xc, xs = nvfp4_quantize(x_bf16, alpha_x, codes, scales, layout)
-    return nvfp4_gemm(xc, xs, alpha_x, w_codes, w_scales, alpha_w, out, y, layout)
+    return nvfp4_gemm_ws(xc, xs, alpha_x, w_codes, w_scales, alpha_w, workspace, out, y, layout)
 
 
 def mfma_probe(iters: int = 4000) -> float:

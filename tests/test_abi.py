@@ -71,9 +71,34 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 48, None, 8, 0, 1, None) == 2
     assert lib.nvfp4_gemm(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 0, None) == 1
     assert lib.nvfp4_gemm(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, 0, None) == 0
+    # the workspace variant validates like nvfp4_gemm, plus its two extra arguments
+    assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 4, 4, 40, None, 8, 0, 0, None, 0, None) == 2
+    assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 0, None, -8, None) == 2
+    assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 0, None, 64, None) == 1
+    assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, 0, None, 64, None) == 0
     assert lib.bf16_gemm(None, 64, None, 64, 4, 4, 64, None, 8, 0, None) == 1
     assert lib.bf16_gemm(None, 32, None, 64, 4, 4, 64, None, 8, 0, None) == 2
     assert lib.nvfp4_global_scale(None, 4, 64, 64, None, None) == 1
+
+
+def test_workspace_size_query(lib):
+    """Host-only: slabs are offered for problems with fewer than 64 output tiles of 128x128 whose K
+    is long enough, the size is slabs * M * N * 4 bytes and never exceeds one 128x128 FP32 tile per
+    compute unit of the largest gfx950 part (256 x 64 KiB)."""
+    q = lib.mq_gemm_workspace_bytes
+    assert q(8192, 4096, 4096) == 0          # 2048 tiles
+    assert q(128, 28672, 4096) == 0          # 224 tiles
+    assert q(128, 4096, 448) == 0            # 7 K steps: nothing to cut
+    assert q(128, 4098, 4096) == 0           # N % 4 != 0
+    assert q(128, 4096, 4080) == 0           # K % 64 != 0
+    assert q(0, 4096, 4096) == 0 and q(128, 0, 4096) == 0 and q(128, 4096, 0) == 0
+    for M, N, K in [(128, 4096, 4096), (64, 4096, 14336), (300, 1024, 8192), (17, 136, 65536)]:
+        b = q(M, N, K)
+        assert b > 0 and b % (M * N * 4) == 0
+        slabs = b // (M * N * 4)
+        tiles = -(-M // 128) * -(-N // 128)
+        assert 2 <= slabs <= min(256 // tiles, K // 512)
+        assert b <= 256 * 128 * 128 * 4
 
 
 def test_binding_refuses_cpu_tensors():

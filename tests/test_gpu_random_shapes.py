@@ -1,6 +1,6 @@
 """GPU parity on seeded random shapes: quantize in either layout, multiply, compare with the
 oracle.  Small enough that the oracle computes every output; shapes are drawn so that they hit
-the 128x128 LDS-pipelined and the register-direct kernels, the simple kernel (K % 64 != 0), ragged M and N,
+every workgroup shape of the register-direct NVFP4 kernel and the tiled BF16 kernels, the simple kernel (K % 64 != 0), ragged M and N,
 and the decode-shape BF16 kernel."""
 import numpy as np
 import pytest

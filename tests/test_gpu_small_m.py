@@ -1,0 +1,126 @@
+"""GPU parity of the NVFP4 product on prefill chunks of a few hundred tokens, where K is cut
+into slabs across workgroups and the partial sums pass through a caller-owned workspace
+(nvfp4_gemm_ws), and of the same shapes without a workspace (four-way split inside a workgroup).
+Every output is compared with the oracle; shapes cover one and several slabs, slabs whose last
+workgroup has waves without any K step, ragged M and N, N % 4 != 0 (no slabs possible) and a
+workspace that is too small for the preferred number of slabs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_20315_amd as mq
+from paper_2605_20315_amd import _lib
+
+from _gpu_util import check_gemm_bf16, check_gemm_fp32, dev_scalar, dev_u8, host_bits, to_ktile
+
+pytestmark = pytest.mark.gpu
+
+
+def _operands(M, N, K, seed):
+    rng = np.random.default_rng([M, N, K, seed])
+    ac = rng.integers(0, 256, size=(M, K // 2)).astype(np.uint8)
+    asc = rng.integers(0x28, 0x48, size=(M, K // 16)).astype(np.uint8)
+    bc = rng.integers(0, 256, size=(N, K // 2)).astype(np.uint8)
+    bsc = rng.integers(0x28, 0x48, size=(N, K // 16)).astype(np.uint8)
+    return ac, asc, np.float32(0.5), bc, bsc, np.float32(3.0)
+
+
+def _reference(ac, asc, aa, bc, bsc, ba):
+    a = oracle.dequantize(ac, asc, aa)
+    b = oracle.dequantize(bc, bsc, ba)
+    return oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b)
+
+
+# (M, N, K): K / 64 K steps; with 256 compute units the launcher picks up to min(256 / tiles, K / 512)
+# slabs.  (100, 520, 4096): 5 tiles, 8 slabs; (128, 4096, 14336): 32 tiles, 7 slabs, 224 K steps
+# do not divide evenly; (300, 264, 1024): 9 tiles, 2 slabs; (64, 1032, 1536): 3 slabs of 8 steps;
+# (17, 136, 8192): 2 tiles, 16 slabs; (130, 2048, 1088): 17 K steps, slabs with idle waves.
+SHAPES = [(100, 520, 4096), (128, 4096, 14336), (300, 264, 1024), (64, 1032, 1536), (17, 136, 8192),
+          (130, 2048, 1088), (1, 8, 1024)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("layout", [mq.MQ_LAYOUT_KTILE, mq.MQ_LAYOUT_LINEAR])
+def test_small_m_with_and_without_workspace(M, N, K, layout):
+    ops = _operands(M, N, K, 0)
+    ref, na, nb = _reference(*ops)
+    ac, asc, aa, bc, bsc, ba = ops
+    arrs = (to_ktile(ac, asc) + to_ktile(bc, bsc)) if layout == mq.MQ_LAYOUT_KTILE else (ac, asc, bc, bsc)
+    d = [dev_u8(t) for t in arrs]
+    a_al, b_al = dev_scalar(aa), dev_scalar(ba)
+    need = mq.mq_gemm_workspace_bytes(M, N, K)
+    assert 0 <= need <= 16 << 20
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    for out in (mq.MQ_OUT_BF16, mq.MQ_OUT_FP32):
+        ys = [mq.nvfp4_gemm(d[0], d[1], a_al, d[2], d[3], b_al, out, layout=layout),
+              mq.nvfp4_gemm_ws(d[0], d[1], a_al, d[2], d[3], b_al, ws, out, layout=layout),
+              mq.nvfp4_gemm_ws(d[0], d[1], a_al, d[2], d[3], b_al, ws, out, layout=layout)]
+        torch.cuda.synchronize()
+        assert torch.equal(ys[1], ys[2])  # bit-identical from run to run
+        for y in ys[:2]:
+            if out == mq.MQ_OUT_BF16:
+                check_gemm_bf16(host_bits(y), ref, na, nb)
+            else:
+                check_gemm_fp32(y.cpu().numpy(), ref, na, nb)
+
+
+def test_workspace_size_limits_the_slabs_and_odd_n_uses_none():
+    M, N, K = 96, 1024, 8192
+    ops = _operands(M, N, K, 1)
+    ref, na, nb = _reference(*ops)
+    ac, asc, aa, bc, bsc, ba = ops
+    d = [dev_u8(t) for t in to_ktile(ac, asc) + to_ktile(bc, bsc)]
+    a_al, b_al = dev_scalar(aa), dev_scalar(ba)
+    need = mq.mq_gemm_workspace_bytes(M, N, K)
+    assert need >= 2 * M * N * 4
+    # room for exactly two slabs, for one (= none are used), for a fraction of one, and an unaligned size
+    for nbytes in (2 * M * N * 4, M * N * 4, 100, need - 4):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        y = mq.nvfp4_gemm_ws(d[0], d[1], a_al, d[2], d[3], b_al, ws, mq.MQ_OUT_FP32, layout=mq.MQ_LAYOUT_KTILE)
+        torch.cuda.synchronize()
+        check_gemm_fp32(y.cpu().numpy(), ref, na, nb)
+    # N % 4 != 0: the second pass works on groups of four columns, so no slabs; the result must be right
+    M, N, K = 40, 1030, 2048
+    assert mq.mq_gemm_workspace_bytes(M, N, K) == 0
+    ops = _operands(M, N, K, 2)
+    ref, na, nb = _reference(*ops)
+    ac, asc, aa, bc, bsc, ba = ops
+    d = [dev_u8(t) for t in to_ktile(ac, asc) + to_ktile(bc, bsc)]
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    ld = 1032
+    buf = torch.full((M, ld), -3.0, dtype=torch.bfloat16, device="cuda")
+    mq.nvfp4_gemm_ws(d[0], d[1], dev_scalar(aa), d[2], d[3], dev_scalar(ba), ws, mq.MQ_OUT_BF16, buf[:, :N],
+                     mq.MQ_LAYOUT_KTILE)
+    torch.cuda.synchronize()
+    check_gemm_bf16(host_bits(buf[:, :N]), ref, na, nb)
+    assert bool((buf[:, N:] == -3.0).all())
+
+
+def test_slabs_into_a_column_slice_and_workspace_argument_checks():
+    M, N, K = 120, 520, 4096
+    ops = _operands(M, N, K, 3)
+    ref, na, nb = _reference(*ops)
+    ac, asc, aa, bc, bsc, ba = ops
+    d = [dev_u8(t) for t in to_ktile(ac, asc) + to_ktile(bc, bsc)]
+    a_al, b_al = dev_scalar(aa), dev_scalar(ba)
+    ws = torch.empty(mq.mq_gemm_workspace_bytes(M, N, K), dtype=torch.uint8, device="cuda")
+    buf = torch.full((M + 1, N + 32), 5.0, dtype=torch.bfloat16, device="cuda")
+    view = buf[:M, 16:16 + N]
+    mq.nvfp4_gemm_ws(d[0], d[1], a_al, d[2], d[3], b_al, ws, mq.MQ_OUT_BF16, view, mq.MQ_LAYOUT_KTILE)
+    torch.cuda.synchronize()
+    check_gemm_bf16(host_bits(view), ref, na, nb)
+    rest = buf.clone()
+    rest[:M, 16:16 + N] = 5.0
+    assert bool((rest == 5.0).all())
+
+    lib = _lib.load()
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    args = [d[0].data_ptr(), d[1].data_ptr(), a_al.data_ptr(), d[2].data_ptr(), d[3].data_ptr(), b_al.data_ptr(),
+            M, N, K, y.data_ptr(), N, mq.MQ_OUT_BF16, mq.MQ_LAYOUT_KTILE]
+    assert lib.nvfp4_gemm_ws(*args, ws.data_ptr() + 4, 1 << 20, 0) == 3      # MQ_ERR_ALIGN
+    assert lib.nvfp4_gemm_ws(*args, ws.data_ptr(), -1, 0) == 2           # MQ_ERR_SHAPE
+    assert lib.nvfp4_gemm_ws(*args, None, 0, 0) == _lib.MQ_OK       # no workspace: same as nvfp4_gemm
+    assert lib.nvfp4_gemm_ws(*args, None, 1 << 20, 0) == _lib.MQ_OK  # NULL with a size: treated as none
+    torch.cuda.synchronize()
+    check_gemm_bf16(host_bits(y), ref, na, nb)
