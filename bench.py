@@ -4,7 +4,7 @@
 One "step" is one pass of the whole hot path over one synthetic prefill batch of the headline
 workload (Llama-3-8B-shaped linears at M = 8192 tokens): for each of the four layers, quantize
 the BF16 activations to NVFP4 on the fly (nvfp4_quantize) and run the block-scaled GEMM against
-the offline-quantized weights (nvfp4_gemm, BF16 out).  Inputs are resident in HBM before the
+the offline-quantized weights (nvfp4_gemm_ws, BF16 out).  Inputs are resident in HBM before the
 timed region; tensor-level scales and weight quantization are computed once, untimed.
 
 Prints ONE JSON line.  `value` = 2*M*N*K summed over the four layers / step time, in TFLOP/s.
@@ -13,7 +13,7 @@ the launch stream (-> roofline), the quantizer's bandwidth, the in-repo BF16 GEM
 shapes (-> speed-up), and the CPU oracle on a bounded sample (-> cpu_baseline).  Further lines of
 the same JSON object, all outside the timed region: the vendor library's BF16 GEMM as context,
 the dynamic-alpha pipeline, decode-shape weight streaming, the producer-fused quantizers and
-the MLP block as a dependent chain, a tokens-per-batch sweep (512 .. 131072), and the rate an
+the MLP block as a dependent chain, a tokens-per-batch sweep (64 .. 131072), and the rate an
 MFMA-only loop sustains on this machine.
 """
 from __future__ import annotations
@@ -65,6 +65,9 @@ def main() -> int:
     cfg = wl.configs()[args.config]
     M = cfg.M
     LAYOUT = mq.MQ_LAYOUT_KTILE     # K-step-major NVFP4 bytes: the layout the GEMM streams
+    # caller-owned workspace of the NVFP4 product (used only below about 512 tokens, where K is
+    # cut into slabs across workgroups); the library's largest request is 16 MiB
+    GEMM_WS = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -94,7 +97,7 @@ def main() -> int:
             mq.nvfp4_quantize(L["x"], L["ax"], L["xc"], L["xs"], LAYOUT)
             if events is not None:
                 e[1].record()
-            mq.nvfp4_gemm(L["xc"], L["xs"], L["ax"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], LAYOUT)
+            mq.nvfp4_gemm_ws(L["xc"], L["xs"], L["ax"], L["wc"], L["ws"], L["aw"], GEMM_WS, mq.MQ_OUT_BF16, L["y"], LAYOUT)
             if events is not None:
                 e[2].record()
                 events.append(e)
@@ -134,7 +137,7 @@ def main() -> int:
         for L in layers:
             mq.nvfp4_global_scale(L["x"], L["ax_dyn"])
             mq.nvfp4_quantize(L["x"], L["ax_dyn"], L["xc"], L["xs"], LAYOUT)
-            mq.nvfp4_gemm(L["xc"], L["xs"], L["ax_dyn"], L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, L["y"], LAYOUT)
+            mq.nvfp4_gemm_ws(L["xc"], L["xs"], L["ax_dyn"], L["wc"], L["ws"], L["aw"], GEMM_WS, mq.MQ_OUT_BF16, L["y"], LAYOUT)
     for L in layers:
         L["ax_dyn"] = torch.empty(1, dtype=torch.float32, device="cuda")
     for _ in range(max(1, args.warmup // 2)):
@@ -252,9 +255,9 @@ def main() -> int:
 
         def mlp_nvfp4():
             mq.nvfp4_quantize_rmsnorm(xh, gw, 1e-6, a_n, ch, sh, LAYOUT)
-            mq.nvfp4_gemm(ch, sh, a_n, Lg["wc"], Lg["ws"], Lg["aw"], mq.MQ_OUT_BF16, yg, LAYOUT)
+            mq.nvfp4_gemm_ws(ch, sh, a_n, Lg["wc"], Lg["ws"], Lg["aw"], GEMM_WS, mq.MQ_OUT_BF16, yg, LAYOUT)
             mq.nvfp4_quantize_silu_mul(yg, a_p, cd, sd, LAYOUT)
-            mq.nvfp4_gemm(cd, sd, a_p, Ld["wc"], Ld["ws"], Ld["aw"], mq.MQ_OUT_BF16, yo, LAYOUT)
+            mq.nvfp4_gemm_ws(cd, sd, a_p, Ld["wc"], Ld["ws"], Ld["aw"], GEMM_WS, mq.MQ_OUT_BF16, yo, LAYOUT)
 
         def mlp_bf16():
             h = torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6)
@@ -278,8 +281,9 @@ def main() -> int:
         sweep = {}
         gen = torch.Generator(device="cuda")
         gen.manual_seed(1234)
-        for ms in (512, 1024, 2048, 4096, 16384, 32768, 65536, 131072):
-            t_q4 = t_b16 = 0.0
+        for ms in (64, 128, 256, 512, 1024, 2048, 4096, 16384, 32768, 65536, 131072):
+            t_q4 = t_b16 = t_ven = 0.0
+            small = ms <= 1024
             for L in layers:
                 K, N = L["layer"].K, L["layer"].N
                 x = torch.randn((ms, K), dtype=torch.bfloat16, device="cuda", generator=gen)
@@ -292,8 +296,14 @@ def main() -> int:
 
                 def one():
                     mq.nvfp4_quantize(x, ax, xc, xs, LAYOUT)
-                    mq.nvfp4_gemm(xc, xs, ax, L["wc"], L["ws"], L["aw"], mq.MQ_OUT_BF16, y, LAYOUT)
-                for fn, reps in ((one, 3), (lambda: mq.bf16_gemm(x, L["w"], mq.MQ_OUT_BF16, y), 2)):
+                    mq.nvfp4_gemm_ws(xc, xs, ax, L["wc"], L["ws"], L["aw"], GEMM_WS, mq.MQ_OUT_BF16, y, LAYOUT)
+
+                def ven():
+                    torch.matmul(x, L["w"].t(), out=y)
+                for fn, reps in ((one, 20 if small else 3),
+                                 (lambda: mq.bf16_gemm(x, L["w"], mq.MQ_OUT_BF16, y), 20 if small else 2),
+                                 (ven, 20 if small else 2)):
+                    fn()
                     fn()
                     s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     s0.record()
@@ -303,13 +313,18 @@ def main() -> int:
                     torch.cuda.synchronize()
                     if fn is one:
                         t_q4 += s0.elapsed_time(s1) / reps
+                    elif fn is ven:
+                        t_ven += s0.elapsed_time(s1) / reps
                     else:
                         t_b16 += s0.elapsed_time(s1) / reps
                 del x, xc, xs, y
             fl = sum(wl.layer_flops(ms, L["layer"]) for L in layers)
             sweep[f"M={ms}"] = {"nvfp4_quant_plus_gemm_tflops": round(fl / (t_q4 * 1e-3) * 1e-12, 1),
                                 "bf16_gemm_tflops": round(fl / (t_b16 * 1e-3) * 1e-12, 1),
-                                "x_vs_bf16_gemm": round(t_b16 / t_q4, 3)}
+                                "vendor_library_bf16_gemm_tflops": round(fl / (t_ven * 1e-3) * 1e-12, 1),
+                                "nvfp4_us": round(t_q4 * 1e3, 1),
+                                "x_vs_bf16_gemm": round(t_b16 / t_q4, 3),
+                                "x_vs_vendor_library_bf16_gemm": round(t_ven / t_q4, 3)}
             torch.cuda.empty_cache()
 
     # ---- what the matrix pipe sustains on this machine for random FP16 operands (measured roof) ----
