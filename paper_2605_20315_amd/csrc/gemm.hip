@@ -683,8 +683,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
         phase(fra[1], frb[1], fra[0], frb[0], 2, cur, 0, 0, U_N{}, U_N{});
         phase(fra[0], frb[0], fra[1], frb[1], 3, cur, 0, 0, U_N{}, U_N{});
         // tile kt+1 has landed in this wave's share of stage nxt; after the barrier in everyone's,
-        // and nobody reads stage cur any more: it receives tile kt+2
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // and nobody reads stage cur any more (this wave's last fragment reads of it have
+        // returned: lgkmcnt, which the MFMAs behind the barrier would wait for anyway): it
+        // receives tile kt+2
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __syncthreads();
         phase(fra[1], frb[1], fra[0], frb[0], 0, nxt, kt + 2, cur, U_0{}, U_H{});
     };
