@@ -26,6 +26,9 @@
  *                                 g = 16 consecutive K elements
  *    alpha  : one float           the tensor-level scale
  * with value x_hat[r, k] = alpha * E4M3(scales[r, k/16]) * E2M1(code[r, k])   (Eq. 1, right).
+ * Scale bytes are what Eq. 2 produces: non-negative and finite, 0x00 .. 0x7E.  The quantizers
+ * emit nothing else; nvfp4_gemm given a byte with the sign bit set or the NaN pattern 0x7F
+ * returns unspecified values for the outputs that the block touches (never a fault).
  */
 #ifndef MIXQUANT_H
 #define MIXQUANT_H
