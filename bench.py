@@ -393,12 +393,13 @@ def main() -> int:
     # ---- the CPU oracle on a bounded sample of the same workload (reported baseline) ----
     if not args.no_cpu_baseline:
         import oracle
-        L = next(l for l in layers if l["x_bits"] is not None)
+        li_sample, L = next((i, l) for i, l in enumerate(layers) if l["x_bits"] is not None)
         rows = min(args.cpu_sample_rows, M)
         xb = L["x_bits"][:rows]
-        ax, aw = np.float32(L["ax"].item()), np.float32(L["aw"].item())
-        wc_d, ws_d = mq.nvfp4_quantize(L["w"], L["aw"])      # canonical byte order for the oracle
-        wc, ws = wc_d.cpu().numpy(), ws_d.cpu().numpy()
+        # everything the oracle sees comes from the seeded generator and the oracle itself
+        w_bits = wl.weight(cfg, li_sample)
+        ax, aw = oracle.global_scale(L["x_bits"]), oracle.global_scale(w_bits)
+        wc, ws = oracle.quantize(w_bits, aw)
         c0 = time.perf_counter()
         xc, xs = oracle.quantize(xb, ax)
         a = oracle.dequantize(xc, xs, ax)

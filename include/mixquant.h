@@ -1,7 +1,7 @@
 /*
  * mixquant.h -- C ABI of the MI355X (gfx950) library for the prefill linear layer of
- * Mix-Quant run as NVFP4 W4A4 (Section 3.3, "NVFP4 Microscaling Quantization for
- * Prefilling"): on-the-fly activation quantization (Eq. 2 then Eq. 1) followed by a
+ * Mix-Quant run as NVFP4 W4A4 (Section 3.3, the paragraph on NVFP4 quantization of the
+ * prefill phase): on-the-fly activation quantization (Eq. 2 then Eq. 1) followed by a
  * block-scaled FP4 GEMM against offline-quantized weights, plus a plain BF16 GEMM that
  * stands for the high-precision decode path the paper compares against.
  *
@@ -13,12 +13,19 @@
  *  - Tensor-level scales (alpha in Eq. 1) are read from device memory, so a scale computed
  *    on the device needs no host round trip.
  *  - Return value: MQ_OK, or an mq_status error.  Arguments are validated on the host before
- *    anything is launched; on error nothing has been enqueued.  MQ_ERR_HIP means the HIP
- *    runtime refused a launch; mq_last_hip_error() returns its hipError_t.
+ *    anything is launched: with any status but MQ_ERR_HIP nothing has been enqueued.
+ *    MQ_ERR_HIP means the HIP runtime refused a launch (mq_last_hip_error() returns its
+ *    hipError_t); an entry point that launches several kernels (nvfp4_global_scale, the
+ *    slab-split product) may then have enqueued the earlier ones, and its outputs are undefined.
+ *  - One-time set-up per device (kernel attributes, the address of the static scratch array):
+ *    done by mq_init(), or else by the first product on that device.  A caller that captures
+ *    streams into HIP graphs calls mq_init() once per device beforehand; after that no entry
+ *    point does anything but enqueue kernels.
  *  - Outputs must not overlap inputs.
  *
  * NVFP4 tensor (Section 3.3): a [rows, K] matrix whose contraction index K is contiguous
- * ("layouts aligned with the GEMM dimension"), K % 16 == 0, stored as
+ * (the scale blocks run along the GEMM's contraction dimension, Section 3.3, last sentence),
+ * K % 16 == 0, stored as
  *    codes  : uint8 [rows, K/2]   element k of a row in byte k/2, even k in the low nibble;
  *                                 a code is E2M1: bit3 sign, bits2..1 exponent (bias 1),
  *                                 bit0 mantissa -> {0, .5, 1, 1.5, 2, 3, 4, 6}
@@ -46,7 +53,8 @@ typedef enum {
     MQ_ERR_SHAPE = 2,  /* rows/M/N < 0, K <= 0, K % 16 != 0 (K % 64 != 0 for MQ_LAYOUT_KTILE), ld too small */
     MQ_ERR_ALIGN = 3,  /* a pointer or leading dimension breaks the stated alignment */
     MQ_ERR_ARG = 4,    /* unknown enum value */
-    MQ_ERR_HIP = 5     /* kernel launch failed; see mq_last_hip_error() */
+    MQ_ERR_HIP = 5,    /* kernel launch failed; see mq_last_hip_error() */
+    MQ_ERR_SCRATCH = 6 /* nvfp4_gemm_noalloc: the problem wants more scratch than its static array holds */
 } mq_status;
 
 typedef enum {
@@ -58,8 +66,8 @@ typedef enum {
  * Byte order of the two arrays of an NVFP4 tensor.
  * MQ_LAYOUT_LINEAR is the canonical order described at the top of this file.
  * MQ_LAYOUT_KTILE (needs K % 64 == 0) stores the same bytes K-step-major, so that the 64-wide
- * K step the GEMM consumes is contiguous over rows ("layouts aligned with the GEMM dimension",
- * Section 3.3):
+ * K step the GEMM consumes is contiguous over rows (one way to lay the blocks out along the
+ * contraction dimension, which is all that Section 3.3 asks of the layout):
  *    codes_ktile [(t * rows + r) * 32 + j] = codes_linear [r * (K/2)  + t * 32 + j],  j < 32
  *    scales_ktile[(t * rows + r) * 4  + j] = scales_linear[r * (K/16) + t * 4  + j],  j < 4
  * for K step t = 0 .. K/64 - 1.  Sizes are the same in both layouts.
@@ -69,13 +77,20 @@ typedef enum {
     MQ_LAYOUT_KTILE = 1
 } mq_layout;
 
+/*
+ * One-time set-up of the current device (hipGetDevice): raises the dynamic-LDS limits of the
+ * tiled kernels and looks up this device's copy of the static scratch array.  Idempotent,
+ * thread-safe, launches nothing.  Optional except before stream capture (see above).
+ */
+int mq_init(void);
+
 /* Sizes, in bytes, of the two byte arrays of an NVFP4 tensor (0 when K % 16 != 0). */
 size_t mq_codes_bytes(int64_t rows, int64_t K);
 size_t mq_scales_bytes(int64_t rows, int64_t K);
 
 /*
- * Tensor-level scale (Section 3.3: the scale that "controls the global dynamic range"; the
- * paper gives no formula, the workloads use alpha = max|x| / (6 * 448)).
+ * Tensor-level scale (Section 3.3 gives it the role of setting the tensor's overall range and
+ * no formula; the workloads use alpha = max|x| / (6 * 448)).
  * Writes alpha = max|x| / 2688 to *alpha_dev (1.0f when the tensor is all zero), all in
  * binary32.  x_bf16: [rows, K] BF16, row stride ldx elements (ldx >= K).  K % 16 == 0,
  * x_bf16 16-byte aligned, ldx % 8 == 0.  rows == 0 writes 1.0f.
@@ -102,8 +117,9 @@ int nvfp4_quantize(const void *x_bf16, int64_t rows, int64_t K, int64_t ldx,
                    void *stream);
 
 /*
- * Quantizer fused with the operation that produces the activation ("quantization ... can be
- * fused efficiently by the backend", Section 3.3).  The paper does not define the producers;
+ * Quantizer fused with the operation that produces the activation (Section 3.3, last sentence:
+ * the layout is chosen so that a backend can fuse quantization with its neighbours).  The paper
+ * does not define the producers;
  * these are the two that feed the linear layers of the decoder blocks of the models it
  * evaluates (Section 4.1), by their textbook definitions.  In both, the producer's value is
  * computed in binary32, rounded once to BF16 (nearest even), and that BF16 tensor is quantized
@@ -130,8 +146,8 @@ int nvfp4_quantize_rmsnorm(const void *x_bf16, int64_t rows, int64_t K, int64_t 
                            int layout, void *y_bf16, int64_t ldy, void *stream);
 
 /*
- * Offline weight pre-pack (weights are static across requests, Section 3.3 "Prefill-Decode
- * Disaggregation Deployment"): copy an NVFP4 tensor from one mq_layout to the other.  Pure byte
+ * Offline weight pre-pack (weights are static across requests: Section 3.3, the paragraph on
+ * the disaggregated deployment): copy an NVFP4 tensor from one mq_layout to the other.  Pure byte
  * permutation by the index map given at mq_layout; src and dst must not overlap.
  * K % 64 == 0; code arrays 16-byte aligned, scale arrays 4-byte aligned; from_layout != to_layout.
  */
@@ -176,6 +192,24 @@ int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *
                   const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev,
                   int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout,
                   void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * The same product for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments,
+ * requirements, results (bit-identical) and tolerance as nvfp4_gemm_ws given a workspace of
+ * MQ_NOALLOC_SCRATCH_BYTES; the partial sums of the slab-split product go to a static device
+ * array of that size inside the library, one copy per GPU, held until the process ends.  The
+ * call allocates nothing and frees nothing.  A problem for which mq_gemm_workspace_bytes(M, N, K)
+ * exceeds MQ_NOALLOC_SCRATCH_BYTES is rejected with MQ_ERR_SCRATCH before anything is enqueued.
+ * Every call on a GPU uses that GPU's one array (nothing in it needs to start at zero: each
+ * slab is written before it is read): calls that overlap in time on one GPU, from different
+ * streams or threads, race on it; calls on one stream are ordered and safe.
+ */
+#define MQ_NOALLOC_SCRATCH_BYTES (16u << 20)
+int nvfp4_gemm_noalloc(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+                       const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev,
+                       int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout,
+                       void *stream);
 
 /*
  * High-precision baseline (the BF16 path that decoding keeps and that the paper's prefill

@@ -15,6 +15,7 @@ from .ref import (  # noqa: F401
     e4m3_round,
     e4m3_value,
     fp4_round,
+    from_ktile,
     gemm_f64,
     global_scale,
     num_threads,
@@ -22,4 +23,5 @@ from .ref import (  # noqa: F401
     rmsnorm_f64,
     row_norms,
     silu_mul_f64,
+    to_ktile,
 )

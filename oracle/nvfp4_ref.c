@@ -1,6 +1,6 @@
 /*
- * CPU oracle for the NVFP4 prefill linear path of Mix-Quant (Section 3.3, "NVFP4
- * Microscaling Quantization for Prefilling", Eq. 1 and Eq. 2).
+ * CPU oracle for the NVFP4 prefill linear path of Mix-Quant (Section 3.3, the paragraph on
+ * NVFP4 quantization of the prefill phase, Eq. 1 and Eq. 2).
  *
  * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, scalar statement of what the path
  * computes, used only by the tests, the smoke check and the benchmark's cpu_baseline leg.
@@ -188,6 +188,38 @@ int nvfp4_ref_quantize(const uint16_t *x, int64_t rows, int64_t K, int64_t ldx, 
     return 0;
 }
 
+/* ---------- K-step-major byte order of an NVFP4 tensor --------------------------------- */
+
+/* Section 3.3 (last sentence) places the blocks along the GEMM's contraction dimension and
+ * leaves the byte order in memory open.  Besides the canonical row-major order written by
+ * nvfp4_ref_quantize(), the library defines a second one in which the bytes of one 64-wide K
+ * step are contiguous over rows: for K step t, row r, the 32 code bytes and the 4 scale bytes
+ * of that (row, step) pair sit at
+ *     codes_ktile [(t * rows + r) * 32 + j] = codes_linear [r * (K/2)  + t * 32 + j],  j < 32
+ *     scales_ktile[(t * rows + r) * 4  + j] = scales_linear[r * (K/16) + t * 4  + j],  j < 4.
+ * Pure permutation, stated here as the three loops of that sentence.  to_ktile != 0 converts
+ * canonical -> K-step-major, 0 the other way.  Returns 0, or -1 when K is not a multiple of 64. */
+int nvfp4_ref_relayout(const uint8_t *src_codes, const uint8_t *src_scales, uint8_t *dst_codes,
+                       uint8_t *dst_scales, int64_t rows, int64_t K, int to_ktile)
+{
+    int64_t steps = K / 64, t, r, j;
+    if (K % 64 != 0 || rows < 0) return -1;
+    for (t = 0; t < steps; ++t)
+        for (r = 0; r < rows; ++r) {
+            for (j = 0; j < 32; ++j) {
+                int64_t kt = (t * rows + r) * 32 + j, lin = r * (K / 2) + t * 32 + j;
+                if (to_ktile) dst_codes[kt] = src_codes[lin];
+                else dst_codes[lin] = src_codes[kt];
+            }
+            for (j = 0; j < 4; ++j) {
+                int64_t kt = (t * rows + r) * 4 + j, lin = r * (K / 16) + t * 4 + j;
+                if (to_ktile) dst_scales[kt] = src_scales[lin];
+                else dst_scales[lin] = src_scales[kt];
+            }
+        }
+    return 0;
+}
+
 /* x_hat = alpha * sigma * q (Eq. 1, right), evaluated in binary64: exact, the three factors
  * carry 24 + 4 + 2 significant bits.  out: [rows, K]. */
 int nvfp4_ref_dequantize(const uint8_t *codes, const uint8_t *scales, float alpha,
@@ -265,8 +297,8 @@ void nvfp4_ref_rmsnorm_f64(const uint16_t *x, int64_t rows, int64_t K, int64_t l
 /* ---------- GEMM: the plain definition ---------------------------------------------- */
 
 /* y[m, n] = sum_{k ascending} a[m, k] * b[n, k] in binary64; a: [M, K], b: [N, K],
- * y: [M, N], all dense row-major.  Both operands have the contraction index contiguous,
- * which is the "layout aligned with the GEMM dimension" of Section 3.3. */
+ * y: [M, N], all dense row-major.  Both operands have the contraction index contiguous:
+ * the blocks of Section 3.3 run along it. */
 void nvfp4_ref_gemm_f64(const double *a, const double *b, int64_t M, int64_t N, int64_t K,
                         double *y)
 {

@@ -47,6 +47,7 @@ def _load():
         "nvfp4_ref_global_scale": (f32, [vp, i64, i64, i64]),
         "nvfp4_ref_quantize": (ctypes.c_int, [vp, i64, i64, i64, f32, vp, vp]),
         "nvfp4_ref_dequantize": (ctypes.c_int, [vp, vp, f32, i64, i64, vp]),
+        "nvfp4_ref_relayout": (ctypes.c_int, [vp, vp, vp, vp, i64, i64, ctypes.c_int]),
         "nvfp4_ref_bf16_to_f64": (None, [vp, i64, i64, i64, vp]),
         "nvfp4_ref_gemm_f64": (None, [vp, vp, i64, i64, i64, vp]),
         "nvfp4_ref_silu_mul_f64": (None, [vp, i64, i64, i64, vp]),
@@ -127,6 +128,27 @@ def dequantize(codes: np.ndarray, scales: np.ndarray, alpha) -> np.ndarray:
                                       rows, K, _ptr(out))
     assert rc == 0
     return out
+
+
+def _relayout(codes: np.ndarray, scales: np.ndarray, to_ktile_flag: int):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    rows, K = codes.shape[0], codes.shape[1] * 2
+    assert K % 64 == 0 and scales.shape == (rows, K // BLOCK)
+    oc, os_ = np.empty_like(codes), np.empty_like(scales)
+    rc = _load().nvfp4_ref_relayout(_ptr(codes), _ptr(scales), _ptr(oc), _ptr(os_), rows, K, to_ktile_flag)
+    assert rc == 0
+    return oc, os_
+
+
+def to_ktile(codes: np.ndarray, scales: np.ndarray):
+    """Canonical byte order -> K-step-major byte order (same array shapes, permuted bytes)."""
+    return _relayout(codes, scales, 1)
+
+
+def from_ktile(codes: np.ndarray, scales: np.ndarray):
+    """K-step-major byte order -> canonical byte order."""
+    return _relayout(codes, scales, 0)
 
 
 def bf16_to_f64(x_bf16: np.ndarray) -> np.ndarray:

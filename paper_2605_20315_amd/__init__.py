@@ -9,7 +9,9 @@ from .ops import (  # noqa: F401
     bf16_gemm,
     mfma_probe,
     mq_gemm_workspace_bytes,
+    mq_init,
     nvfp4_gemm,
+    nvfp4_gemm_noalloc,
     nvfp4_gemm_ws,
     nvfp4_global_scale,
     nvfp4_linear,

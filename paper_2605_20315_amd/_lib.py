@@ -49,6 +49,10 @@ def load() -> ctypes.CDLL:
     lib.nvfp4_gemm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
     lib.nvfp4_gemm_ws.restype = ci
     lib.nvfp4_gemm_ws.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp, i64, vp]
+    lib.nvfp4_gemm_noalloc.restype = ci
+    lib.nvfp4_gemm_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, ci, ci, vp]
+    lib.mq_init.restype = ci
+    lib.mq_init.argtypes = []
     lib.mq_gemm_workspace_bytes.restype = i64
     lib.mq_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.bf16_gemm.restype = ci

@@ -1,5 +1,7 @@
 // extern "C" entry points of libmixquant: argument validation on the host, then one or a
 // few kernel launches on the caller's stream.  Nothing here allocates or synchronises.
+#include <atomic>
+
 #include "mq_common.h"
 
 namespace mq {
@@ -14,6 +16,39 @@ int note_launch(hipError_t e)
 }
 
 static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// One-time set-up per device: kernel attributes (dynamic LDS limits) and, for the entry point
+// that may not allocate, the address of this device's copy of the static scratch array.
+constexpr int kMaxDevices = 64;
+static std::atomic<int> g_device_ready[kMaxDevices];
+static void *g_scratch_ptr[kMaxDevices];
+
+}  // namespace mq
+
+// Scratch memory of nvfp4_gemm_noalloc: FP32 partial sums of the slab-split product.  Every GPU
+// the library runs on holds its own copy until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress; kernels receive the per-device address kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[MQ_NOALLOC_SCRATCH_BYTES];
+
+namespace mq {
+
+// Current device's slot, set up on first use.  Returns MQ_OK or MQ_ERR_HIP.
+static int ensure_device(int *slot_out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return note_launch(e);
+    if (dev < 0 || dev >= kMaxDevices) return note_launch(hipErrorInvalidDevice);
+    if (slot_out) *slot_out = dev;
+    if (g_device_ready[dev].load(std::memory_order_acquire)) return MQ_OK;
+    if (int rc = configure_gemm_kernels()) return rc;
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr) return note_launch(e != hipSuccess ? e : hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = ptr;  // two racing threads store the same address
+    g_device_ready[dev].store(1, std::memory_order_release);
+    return MQ_OK;
+}
 
 }  // namespace mq
 
@@ -137,6 +172,8 @@ int64_t mq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return ks >= 2 ? (int64_t)ks * M * N * 4 : 0;
 }
 
+int mq_init(void) { return ensure_device(nullptr); }
+
 int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
                const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
                int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *stream)
@@ -145,10 +182,34 @@ int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_a
                          layout, nullptr, 0, stream);
 }
 
+// Shared body of the three NVFP4 product entry points.  use_static: the workspace is this
+// device's copy of the static scratch array (looked up after the arguments have been validated).
+static int gemm_fp4_entry(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+                          const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
+                          int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *workspace,
+                          int64_t workspace_bytes, bool use_static, void *stream);
+
+int nvfp4_gemm_noalloc(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+                       const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
+                       int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *stream)
+{
+    return gemm_fp4_entry(a_codes, a_scales, a_alpha_dev, b_codes, b_scales, b_alpha_dev, M, N, K, y, ldy, out,
+                          layout, nullptr, 0, true, stream);
+}
+
 int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
                   const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
                   int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *workspace,
                   int64_t workspace_bytes, void *stream)
+{
+    return gemm_fp4_entry(a_codes, a_scales, a_alpha_dev, b_codes, b_scales, b_alpha_dev, M, N, K, y, ldy, out,
+                          layout, workspace, workspace_bytes, false, stream);
+}
+
+static int gemm_fp4_entry(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
+                          const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev, int64_t M,
+                          int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout, void *workspace,
+                          int64_t workspace_bytes, bool use_static, void *stream)
 {
     if (M < 0 || N < 0 || K <= 0 || K % kBlock != 0 || workspace_bytes < 0) return MQ_ERR_SHAPE;
     if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
@@ -164,6 +225,15 @@ int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *
         return MQ_ERR_ALIGN;
     if (K % 64 == 0 && (!aligned(a_scales, 4) || !aligned(b_scales, 4))) return MQ_ERR_ALIGN;
     if (workspace && !aligned(workspace, 16)) return MQ_ERR_ALIGN;
+    // lane offsets are relative to a wave tile of 128 rows and must fit 32 bits
+    if (128 * (K / 2) + 64 >= ((int64_t)1 << 32)) return MQ_ERR_SHAPE;
+    if (use_static && mq_gemm_workspace_bytes(M, N, K) > (int64_t)MQ_NOALLOC_SCRATCH_BYTES) return MQ_ERR_SCRATCH;
+    int dev = 0;
+    if (int rc2 = ensure_device(&dev)) return rc2;
+    if (use_static) {
+        workspace = g_scratch_ptr[dev];
+        workspace_bytes = (int64_t)MQ_NOALLOC_SCRATCH_BYTES;
+    }
     GemmArgs g{};
     g.ws = workspace_bytes > 0 ? static_cast<float *>(workspace) : nullptr;
     g.ws_bytes = g.ws ? workspace_bytes : 0;
@@ -188,8 +258,6 @@ int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *
         g.a_s_step = M * 4;
         g.b_s_step = N * 4;
     }
-    const int64_t lim = (int64_t)1 << 32;
-    g.fits32 = M * g.a_c_row + 64 < lim && N * g.b_c_row + 64 < lim;
     g.M = M;
     g.N = N;
     g.K = K;
@@ -214,7 +282,9 @@ int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw, 
     g.b = w_bf16;
     g.lda = ldx;
     g.ldb = ldw;
-    g.fits32 = M * ldx * 2 + 256 < ((int64_t)1 << 32) && N * ldw * 2 + 256 < ((int64_t)1 << 32);
+    // thread offsets are relative to a tile of 256 rows and must fit 32 bits
+    if (256 * (ldx > ldw ? ldx : ldw) * 2 + 256 >= ((int64_t)1 << 32)) return MQ_ERR_SHAPE;
+    if (int rc = ensure_device(nullptr)) return rc;
     g.M = M;
     g.N = N;
     g.K = K;
@@ -242,12 +312,15 @@ const char *mq_status_string(int status)
     case MQ_ERR_ALIGN: return "MQ_ERR_ALIGN: pointer or leading dimension breaks the required alignment";
     case MQ_ERR_ARG: return "MQ_ERR_ARG: unknown enum value";
     case MQ_ERR_HIP: return "MQ_ERR_HIP: kernel launch failed (see mq_last_hip_error)";
+    case MQ_ERR_SCRATCH:
+        return "MQ_ERR_SCRATCH: the problem wants more scratch memory than the static array of "
+               "nvfp4_gemm_noalloc holds (use nvfp4_gemm_ws with a workspace)";
     default: return "unknown mq_status";
     }
 }
 
 int mq_last_hip_error(void) { return g_last_hip_error; }
 
-const char *mq_version(void) { return "0.1"; }
+const char *mq_version(void) { return "0.2"; }
 
 }  // extern "C"

@@ -235,16 +235,27 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     // (scalar arithmetic only), plus the lane's row and half as a 32-bit vector offset.  Rows
     // are clamped below, so every access is in bounds by construction and the resources carry
     // the maximal size.
+    // The lane offsets are relative to the first row of the wave tile (whose 64-bit address is
+    // scalar), so they fit 32 bits for any operand size.
     uint32_t vc[8], vs[8];
+    const char *ta_c, *tb_c, *ta_s, *tb_s;  // first A / B row of this wave's tile: codes, scales
     auto set_tile = [&](int64_t m0, int64_t n0) {
+        int64_t ra = m0 + wm0, rb = n0 + wn0;
+        ra = ra < g.M ? ra : g.M - 1;
+        rb = rb < g.N ? rb : g.N - 1;
+        ta_c = static_cast<const char *>(g.a) + ra * g.a_c_row;
+        tb_c = static_cast<const char *>(g.b) + rb * g.b_c_row;
+        ta_s = reinterpret_cast<const char *>(g.a_scales) + ra * g.a_s_row;
+        tb_s = reinterpret_cast<const char *>(g.b_scales) + rb * g.b_s_row;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const bool isA = q < 4;
             const int64_t total = isA ? g.M : g.N;
             int64_t grow = (isA ? m0 + wm0 + ((q & 3) ^ aswap) * 32 : n0 + wn0 + (q & 3) * 32) + frow;
             grow = grow < total ? grow : total - 1;
-            vc[q] = (uint32_t)(grow * (isA ? g.a_c_row : g.b_c_row) + fhalf * 16);
-            vs[q] = (uint32_t)(grow * (isA ? g.a_s_row : g.b_s_row));
+            const int64_t rel = grow - (isA ? ra : rb);  // 0 .. 127
+            vc[q] = (uint32_t)(rel * (isA ? g.a_c_row : g.b_c_row) + fhalf * 16);
+            vs[q] = (uint32_t)(rel * (isA ? g.a_s_row : g.b_s_row));
         }
     };
     RawTile st[NSETS];
@@ -254,9 +265,9 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
             return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(static_cast<const char *>(base)) + off, 0, -1,
                                                      0x00020000);
         };
-        const __amdgpu_buffer_rsrc_t rac = rsrc(g.a, (int64_t)t * g.a_c_step), rbc = rsrc(g.b, (int64_t)t * g.b_c_step);
-        const __amdgpu_buffer_rsrc_t ras = rsrc(g.a_scales, (int64_t)t * g.a_s_step);
-        const __amdgpu_buffer_rsrc_t rbs = rsrc(g.b_scales, (int64_t)t * g.b_s_step);
+        const __amdgpu_buffer_rsrc_t rac = rsrc(ta_c, (int64_t)t * g.a_c_step), rbc = rsrc(tb_c, (int64_t)t * g.b_c_step);
+        const __amdgpu_buffer_rsrc_t ras = rsrc(ta_s, (int64_t)t * g.a_s_step);
+        const __amdgpu_buffer_rsrc_t rbs = rsrc(tb_s, (int64_t)t * g.b_s_step);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < 4 ? rac : rbc, (int)vc[q], 0, 0);
@@ -462,8 +473,10 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
 
     // chunk j of this thread: row (tid>>3) + j*(THREADS/8) of the tile, 16-byte chunk tid&7 of its 128 bytes
     constexpr int NL = C::LA + C::LB;
-    uint32_t vo[NL];  // global byte offsets (K step 0)
+    uint32_t vo[NL];  // global byte offsets from the tile's first row (K step 0): 32 bits for any operand size
     int wad[NL];      // LDS byte addresses (stage 0)
+    const char *const ta = static_cast<const char *>(g.a) + m0 * g.lda * 2;  // m0 < M, n0 < N
+    const char *const tb = static_cast<const char *>(g.b) + n0 * g.ldb * 2;
 #pragma unroll
     for (int j = 0; j < NL; ++j) {
         const bool isA = j < C::LA;
@@ -471,14 +484,14 @@ __global__ __launch_bounds__(C::THREADS) void gemm_bf16_pipelined(GemmArgs g, in
         int64_t grow = (isA ? m0 : n0) + r;
         const int64_t total = isA ? g.M : g.N;
         grow = grow < total ? grow : total - 1;
-        vo[j] = (uint32_t)(grow * (isA ? g.lda : g.ldb) * 2 + (tid & 7) * 16);
+        vo[j] = (uint32_t)((grow - (isA ? m0 : n0)) * (isA ? g.lda : g.ldb) * 2 + (tid & 7) * 16);
         wad[j] = (isA ? 0 : C::B_BASE) + (r * 8 + ((tid & 7) ^ swz_key(r))) * 16;
     }
     uint4 regs[NL];
     auto load_tile = [&](int t) {
         t = t < KT ? t : KT - 1;
-        const char *a = static_cast<const char *>(g.a) + (int64_t)t * (BK * 2);
-        const char *b = static_cast<const char *>(g.b) + (int64_t)t * (BK * 2);
+        const char *a = ta + (int64_t)t * (BK * 2);
+        const char *b = tb + (int64_t)t * (BK * 2);
 #pragma unroll
         for (int j = 0; j < NL; ++j) regs[j] = *reinterpret_cast<const uint4 *>((j < C::LA ? a : b) + vo[j]);
     };
@@ -594,7 +607,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
     const int KT = (int)(g.K / BK);
 
     // load u of this wave: rows 8 * (wave * GA + u) .. + 7 of the A tile (u < GA), else of the B tile
+    // byte offsets from the tile's first row: 32 bits for any operand size
     uint32_t vo[NL];
+    const char *const ta = static_cast<const char *>(g.a) + m0 * g.lda * 2;  // m0 < M, n0 < N
+    const char *const tb = static_cast<const char *>(g.b) + n0 * g.ldb * 2;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
         const bool isA = u < GA;
@@ -602,7 +618,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
         int64_t grow = (isA ? m0 : n0) + r;
         const int64_t total = isA ? g.M : g.N;
         grow = grow < total ? grow : total - 1;
-        vo[u] = (uint32_t)(grow * (isA ? g.lda : g.ldb) * 2 + (((lane & 7) ^ swz_key(r)) * 16));
+        vo[u] = (uint32_t)((grow - (isA ? m0 : n0)) * (isA ? g.lda : g.ldb) * 2 + (((lane & 7) ^ swz_key(r)) * 16));
     }
     // LDS byte address of the dynamic segment
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)L;
@@ -610,13 +626,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_d2l(GemmArgs g, int tiles_m, in
     auto load_group = [&](int t, int stage, int u) {
         t = t < KT ? t : KT - 1;
         const bool isA = u < GA;
-        const char *base = static_cast<const char *>(isA ? g.a : g.b) + (int64_t)t * (BK * 2);
+        const char *base = (isA ? ta : tb) + (int64_t)t * (BK * 2);
         const uint32_t dst = lds0 + (isA ? stage * C::A_STAGE + (wave * GA + u) * 1024
                                          : C::B_BASE + stage * C::B_STAGE + (wave * GB + (u - GA)) * 1024);
+        // m0 is named as clobbered so that the compiler never keeps a value of its own in it across
+        // this statement (it calls m0 "reserved" and warns about any clobber of it: silenced here)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                      :
                      : "s"(dst), "v"(vo[u]), "s"(base)
-                     : "memory");
+                     : "memory", "m0");
+#pragma clang diagnostic pop
     };
     auto load_tile = [&](int t, int stage) {
 #pragma unroll
@@ -908,18 +929,9 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *out, int iters)
 
 // ---- launchers ------------------------------------------------------------------------------
 
-// `configured` remembers that the kernel's dynamic-LDS limit has been raised.  Two threads racing
-// here both set the same attribute to the same value, which is harmless.
 template <class Kern>
-int launch_tiles(Kern kern, size_t lds_bytes, int bm, int bn, int threads, const GemmArgs &g, hipStream_t s,
-                 std::atomic<bool> &configured)
+int launch_tiles(Kern kern, size_t lds_bytes, int bm, int bn, int threads, const GemmArgs &g, hipStream_t s)
 {
-    if (!configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return note_launch(e);
-        configured.store(true, std::memory_order_release);
-    }
     const int64_t tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
     kern<<<dim3((unsigned)(tiles_m * tiles_n)), dim3(threads), lds_bytes, s>>>(g, (int)tiles_m, (int)tiles_n);
@@ -945,14 +957,8 @@ inline int compute_units(int &n)
 
 template <class Kern>
 int launch_persistent(Kern kern, int bm, int bn, size_t lds_bytes, const GemmArgs &g, hipStream_t s, int cus,
-                      std::atomic<bool> &configured, int items_per_tile = 1)
+                      int items_per_tile = 1)
 {
-    if (lds_bytes > 0 && !configured.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return note_launch(e);
-        configured.store(true, std::memory_order_release);
-    }
     const int64_t tiles_m = (g.M + bm - 1) / bm, tiles_n = (g.N + bn - 1) / bn;
     if (tiles_m * tiles_n > 0x7FFFFFFF) return MQ_ERR_SHAPE;
     const int64_t items = tiles_m * tiles_n * items_per_tile;
@@ -1003,12 +1009,11 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         // decode shapes: a few tokens against the whole weight matrix
         if (g.M <= 64 && g.K % 128 == 0 && (g.N + 15) / 16 <= 0x7FFFFFFF) return launch_skinny<OUT_BF16>(g, s);
     }
-    // The tiled kernels step K by 64 and address operands with 32-bit byte offsets.
-    if (g.K % BK != 0 || !g.fits32) return launch_simple<FP4, OUT_BF16>(g, s);
+    // The tiled kernels step K by 64.
+    if (g.K % BK != 0) return launch_simple<FP4, OUT_BF16>(g, s);
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
     using Mid = PCfg<256, 128, 2, 2>;   // BF16 only: 4 waves of 128x64
     using Small = PCfg<128, 128, 2, 2>;  // BF16 only: 4 waves of 64x64
-    static std::atomic<bool> cfg_mid{false}, cfg_small{false};
     const int64_t mid_tiles = ((g.M + 255) / 256) * ((g.N + 127) / 128);
     if constexpr (FP4) {
         // Three workgroup shapes: 256x256 (whole K per wave), 256x128 with K split over wave
@@ -1020,14 +1025,13 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         const int64_t small_tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
         const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus,
                       r4 = (small_tiles + cus - 1) / cus;
-        static std::atomic<bool> cfg_d1{false}, cfg_d2{false}, cfg_d4{false};
         if (2 * small_tiles >= cus) {
             const int64_t c1 = 100 * r1, c2 = 55 * r2, c4 = 34 * r4;
             if (2 * mid_tiles < cus || (c4 < c1 && c4 < c2))
-                return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus, cfg_d4);
+                return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus);
             if (c2 < c1)
-                return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus, cfg_d2);
-            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus, cfg_d1);
+                return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus);
+            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus);
         }
         // Fewer 128x128 tiles than half the compute units (a few hundred tokens): the time is the
         // weights' way from HBM, and only more workgroups pull harder.  With a workspace, K is cut
@@ -1037,15 +1041,13 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         if (ks >= 2) {
             GemmArgs gs = g;
             gs.ksplit = ks;
-            static std::atomic<bool> cfg_x4{false};
-            if (int rc = launch_persistent(gemm_fp4_direct<OUT_BF16, 4, true>, 128, 128, 128 * 1024, gs, s, cus, cfg_x4,
-                                           ks))
+            if (int rc = launch_persistent(gemm_fp4_direct<OUT_BF16, 4, true>, 128, 128, 128 * 1024, gs, s, cus, ks))
                 return rc;
             const int64_t quads = g.M * (g.N / 4);
             splitk_reduce_kernel<OUT_BF16><<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(gs);
             return note_launch(hipGetLastError());
         }
-        return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus, cfg_d4);
+        return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus);
     } else {
         // Same choice by rounds of workgroups as above: 256x256 tiles, or 256x128 tiles (half the
         // work per workgroup, somewhat less efficient) when they waste less of the last round;
@@ -1054,17 +1056,42 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         if (int rc = compute_units(cus)) return rc;
         const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus;
         using D = PCfg<256, 256, 2, 2>;
-        static std::atomic<bool> cfg_d{false};
         if (2 * mid_tiles >= cus && 100 * r1 > 58 * r2)
-            return launch_tiles(gemm_bf16_d2l<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s, cfg_mid);
+            return launch_tiles(gemm_bf16_d2l<Mid, OUT_BF16>, Mid::LDS_BYTES, 256, 128, Mid::THREADS, g, s);
         if (2 * mid_tiles >= cus)
-            return launch_tiles(gemm_bf16_d2l<D, OUT_BF16>, D::LDS_BYTES, 256, 256, D::THREADS, g, s, cfg_d);
-        return launch_tiles(gemm_bf16_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s,
-                            cfg_small);
+            return launch_tiles(gemm_bf16_d2l<D, OUT_BF16>, D::LDS_BYTES, 256, 256, D::THREADS, g, s);
+        return launch_tiles(gemm_bf16_pipelined<Small, OUT_BF16>, Small::LDS_BYTES, 128, 128, Small::THREADS, g, s);
     }
 }
 
 }  // namespace
+
+// Raises the dynamic-LDS limit of every kernel that asks for more than the default.  Done once
+// per device before the first launch (mq_init, or the first product on a device), so that no
+// launch path has one-time work left that a stream capture could trip over.
+int configure_gemm_kernels()
+{
+    auto set = [](auto kern, size_t bytes) {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)bytes);
+    };
+    using D = PCfg<256, 256, 2, 2>;
+    using Mid = PCfg<256, 128, 2, 2>;
+    using Small = PCfg<128, 128, 2, 2>;
+    constexpr size_t X = 128 * 1024;  // accumulator exchange of the K-split variants
+    hipError_t e = hipSuccess;
+    auto both = [&](auto k_bf16, auto k_fp32, size_t bytes) {
+        if (e == hipSuccess) e = set(k_bf16, bytes);
+        if (e == hipSuccess) e = set(k_fp32, bytes);
+    };
+    both(gemm_fp4_direct<true, 2>, gemm_fp4_direct<false, 2>, X);
+    both(gemm_fp4_direct<true, 4>, gemm_fp4_direct<false, 4>, X);
+    both(gemm_fp4_direct<true, 4, true>, gemm_fp4_direct<false, 4, true>, X);
+    both(gemm_bf16_d2l<D, true>, gemm_bf16_d2l<D, false>, D::LDS_BYTES);
+    both(gemm_bf16_d2l<Mid, true>, gemm_bf16_d2l<Mid, false>, Mid::LDS_BYTES);
+    both(gemm_bf16_pipelined<Small, true>, gemm_bf16_pipelined<Small, false>, Small::LDS_BYTES);
+    return note_launch(e);
+}
 
 int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
 {

@@ -50,7 +50,6 @@ struct GemmArgs {
     // r * c_row + t * c_step, the 4 scale bytes at r * s_row + t * s_step (a K step is 64 elements)
     int64_t a_c_row, a_c_step, a_s_row, a_s_step;
     int64_t b_c_row, b_c_step, b_s_row, b_s_step;
-    bool fits32;              // every per-thread byte offset fits 32 bits (else: simple kernel)
     int64_t M, N, K;
     void *y;
     int64_t ldy;
@@ -63,6 +62,8 @@ struct GemmArgs {
 };
 // K slabs the NVFP4 launcher would cut a problem into (1: none), given this much workspace
 int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
+// sets the dynamic-LDS limit of every tiled kernel on the current device (idempotent)
+int configure_gemm_kernels();
 int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);
 int launch_gemm_bf16(const GemmArgs &g, hipStream_t s);
 int launch_mfma_probe(float *out, int iters, int blocks, hipStream_t s);

@@ -144,6 +144,36 @@ def nvfp4_gemm(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int 
     return y
 
 
+def mq_init() -> None:
+    """One-time set-up of the current device (kernel attributes, static scratch address); optional
+    except before capturing the calls into a HIP graph."""
+    _lib.check(_lib.load().mq_init(), "mq_init")
+
+
+NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def nvfp4_gemm_noalloc(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int = MQ_OUT_BF16,
+                       y: torch.Tensor | None = None, layout: int = MQ_LAYOUT_LINEAR) -> torch.Tensor:
+    """nvfp4_gemm_ws with the library's static scratch array as the workspace (allocates nothing;
+    pass `y` to keep the binding from allocating the output)."""
+    _need_gpu(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha)
+    M, K = a_codes.shape[0], a_codes.shape[1] * 2
+    N = b_codes.shape[0]
+    assert b_codes.shape[1] * 2 == K and a_scales.shape == (M, K // BLOCK) and b_scales.shape == (N, K // BLOCK)
+    for t in (a_codes, a_scales, b_codes, b_scales):
+        assert t.dtype == torch.uint8 and t.is_contiguous()
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16 if out == MQ_OUT_BF16 else torch.float32,
+                        device=a_codes.device)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    rc = _lib.load().nvfp4_gemm_noalloc(a_codes.data_ptr(), a_scales.data_ptr(), a_alpha.data_ptr(),
+                                        b_codes.data_ptr(), b_scales.data_ptr(), b_alpha.data_ptr(),
+                                        M, N, K, y.data_ptr(), ldy, out, layout, _stream())
+    _lib.check(rc, "nvfp4_gemm_noalloc")
+    return y
+
+
 def mq_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
     """Workspace size that lets nvfp4_gemm_ws choose its K slabs freely (0: it would use none)."""
     return int(_lib.load().mq_gemm_workspace_bytes(M, N, K))

@@ -32,6 +32,12 @@ def bf16_ordinal(bits: np.ndarray) -> np.ndarray:
     return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
 
 
+# Relative accuracy (in units of ||row|| * ||col||) that the FP32-output path is held to in every
+# test: products are exact, only the FP32 accumulation rounds (measured worst: 9e-9).  The stated
+# bound of the method is 1e-4; this tighter figure is what makes the strict BF16 rule below follow.
+ACC_REL = 1e-7
+
+
 def check_gemm_fp32(y: np.ndarray, y_ref: np.ndarray, norm_a: np.ndarray, norm_b: np.ndarray,
                     rel: float = 1e-4):
     """max |y - Y*| <= rel * ||row|| * ||col||, element by element.  Returns the worst ratio."""
@@ -39,30 +45,39 @@ def check_gemm_fp32(y: np.ndarray, y_ref: np.ndarray, norm_a: np.ndarray, norm_b
     err = np.abs(y.astype(np.float64) - y_ref)
     ok = err <= rel * bound
     assert ok.all(), f"{(~ok).sum()} outputs beyond {rel}*||row||*||col||, worst err {err.max()}"
-    return float((err / np.maximum(bound, 1e-300)).max())
+    worst = float((err / np.maximum(bound, 1e-300)).max())
+    assert worst <= ACC_REL, f"FP32 accumulation error {worst:.2e} * ||row||*||col|| (exact products expected)"
+    return worst
 
 
 def check_gemm_bf16(y_bits: np.ndarray, y_ref: np.ndarray, norm_a: np.ndarray, norm_b: np.ndarray,
                     rel: float = 1e-4):
-    """BF16 acceptance: the output must lie within 1 BF16 ulp of the correctly rounded value of
-    some real number within rel*||row||*||col|| of Y* (an FP32-accumulated sum cannot do better
-    where Y* is a near-cancellation).  Returns the fraction that is within 1 ulp of RNE(Y*) itself."""
-    tau = rel * np.outer(norm_a, norm_b)
+    """BF16 acceptance, two rules, both asserted.
+    Band (every output): within 1 BF16 ulp of the correctly rounded value of some real number
+    within rel*||row||*||col|| of Y* (an FP32-accumulated sum cannot do better where Y* is a
+    near-cancellation).
+    Strict (every output that is not a cancellation, |Y*| >= 2^8 * ACC_REL * ||row||*||col||, where an
+    accumulation error of ACC_REL*||row||*||col|| is below one BF16 ulp of Y*): within 1 BF16 ulp of
+    RNE(Y*) itself; and at least 99.99 % of all outputs when there are enough of them to say so.
+    Returns the fraction of all outputs within 1 ulp of RNE(Y*)."""
+    bound = np.outer(norm_a, norm_b)
+    tau = rel * bound
     lo = bf16_ordinal(oracle.bf16_round(y_ref - tau)) - 1
     hi = bf16_ordinal(oracle.bf16_round(y_ref + tau)) + 1
     got = bf16_ordinal(y_bits)
     ok = (got >= lo) & (got <= hi)
     assert ok.all(), f"{(~ok).sum()} BF16 outputs outside the accepted interval"
     strict = np.abs(got - bf16_ordinal(oracle.bf16_round(y_ref))) <= 1
-    return float(strict.mean())
+    plain = np.abs(y_ref) >= 256.0 * ACC_REL * bound
+    bad = plain & ~strict
+    assert not bad.any(), (f"{bad.sum()} non-cancellation BF16 outputs more than 1 ulp from RNE(Y*), e.g. at "
+                           f"{np.argwhere(bad)[0].tolist()}")
+    frac = float(strict.mean())
+    if strict.size >= 10000:
+        assert frac >= 0.9999, f"only {frac:.6f} of the BF16 outputs within 1 ulp of RNE(Y*)"
+    return frac
 
 
 def to_ktile(codes: np.ndarray, scales: np.ndarray):
-    """The K-step-major byte order, from the canonical linear one, by the documented index map:
-    codes_ktile[t, r, j] = codes_linear[r, t*32 + j], scales_ktile[t, r, j] = scales_linear[r, t*4 + j]."""
-    R, half_k = codes.shape
-    T = half_k // 32
-    assert half_k % 32 == 0 and scales.shape == (R, T * 4)
-    ck = np.ascontiguousarray(codes.reshape(R, T, 32).transpose(1, 0, 2)).reshape(R, half_k)
-    sk = np.ascontiguousarray(scales.reshape(R, T, 4).transpose(1, 0, 2)).reshape(R, T * 4)
-    return ck, sk
+    """The K-step-major byte order from the canonical one: the oracle's plain-loop permutation."""
+    return oracle.to_ktile(codes, scales)

@@ -41,7 +41,7 @@ def test_size_helpers_and_status_strings(lib):
     assert lib.mq_codes_bytes(8192, 4096) == 8192 * 2048
     assert lib.mq_scales_bytes(8192, 4096) == 8192 * 256
     assert lib.mq_codes_bytes(4, 24) == 0 and lib.mq_scales_bytes(-1, 16) == 0
-    for code in range(6):
+    for code in range(7):
         assert lib.mq_status_string(code).decode().startswith("MQ_")
     assert lib.mq_version().decode().count(".") == 1
 
@@ -76,6 +76,9 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 0, None, -8, None) == 2
     assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 4, 4, 64, None, 8, 0, 0, None, 64, None) == 1
     assert lib.nvfp4_gemm_ws(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, 0, None, 64, None) == 0
+    # the allocation-free variant: same validation, no GPU touched on an argument error
+    assert lib.nvfp4_gemm_noalloc(None, None, None, None, None, None, 4, 4, 40, None, 8, 0, 0, None) == 2
+    assert lib.nvfp4_gemm_noalloc(None, None, None, None, None, None, 0, 4, 64, None, 8, 0, 0, None) == 0
     assert lib.bf16_gemm(None, 64, None, 64, 4, 4, 64, None, 8, 0, None) == 1
     assert lib.bf16_gemm(None, 32, None, 64, 4, 4, 64, None, 8, 0, None) == 2
     assert lib.nvfp4_global_scale(None, 4, 64, 64, None, None) == 1

@@ -187,6 +187,34 @@ def test_operand_larger_than_2_gib():
         torch.cuda.empty_cache()
 
 
+@pytest.mark.timeout(600)
+def test_bf16_operand_larger_than_4_gib():
+    """A BF16 activation operand of 4.6 GB: row offsets pass 2^32 bytes.  The tiled kernel addresses
+    rows relative to its tile, so it serves this shape like any other (no slow path)."""
+    M, N, K = 160000, 256, 14336
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4321)
+    x = torch.randn((M, K), dtype=torch.bfloat16, device="cuda", generator=gen)
+    w = (torch.randn((N, K), dtype=torch.float32, device="cuda", generator=gen) * K ** -0.5).to(torch.bfloat16)
+    rng = np.random.default_rng(78)
+    first_past = (1 << 32) // (2 * K)      # first row that starts beyond 4 GiB
+    rows = np.unique(np.concatenate([rng.integers(0, M, 40), [0, 1, 255, 256, first_past - 1, first_past,
+                                                               first_past + 1, M - 257, M - 256, M - 2, M - 1]]))
+    ridx = torch.from_numpy(rows).cuda()
+    a = oracle.bf16_to_f64(host_bits(x[ridx]))
+    b = oracle.bf16_to_f64(host_bits(w))
+    ref = oracle.gemm_f64(a, b)
+    na, nb = oracle.row_norms(a), oracle.row_norms(b)
+    y32 = mq.bf16_gemm(x, w, mq.MQ_OUT_FP32)
+    y16 = mq.bf16_gemm(x, w, mq.MQ_OUT_BF16)
+    torch.cuda.synchronize()
+    check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+    check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
+    assert torch.equal(y32.to(torch.bfloat16), y16)
+    del x, y32, y16
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("K", [64, 192, 448, 1280])
 def test_four_way_split_k_path_with_ragged_edges(K):
     """256 workgroup tiles of 128x128 select the register-direct kernel with K split over its four
@@ -387,7 +415,7 @@ def test_chain_replays_from_a_hip_graph():
         mq.nvfp4_global_scale(x, ax)
         mq.nvfp4_quantize(x, ax, xc, xs, mq.MQ_LAYOUT_KTILE)
         mq.nvfp4_gemm(xc, xs, ax, wc, ws, aw, mq.MQ_OUT_BF16, y, mq.MQ_LAYOUT_KTILE)
-    chain()                                # eager warm-up: one-time kernel attributes are set here
+    mq.mq_init()                           # one-time set-up of the device; no eager warm-up of the chain is needed
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
