@@ -5,6 +5,7 @@ from .ops import (  # noqa: F401
     MQ_LAYOUT_LINEAR,
     MQ_OUT_BF16,
     MQ_OUT_FP32,
+    NOALLOC_SCRATCH_BYTES,
     MixQuantError,
     bf16_gemm,
     mfma_probe,

@@ -168,6 +168,7 @@ static constexpr int kMaxComputeUnits = 256;
 int64_t mq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
+    if (gemm_fp4_small_waves(M, N, K, INT64_MAX, kMaxComputeUnits) > 0) return 0;  // one launch, no partial sums
     const int ks = gemm_fp4_ksplit(M, N, K, INT64_MAX, kMaxComputeUnits);
     return ks >= 2 ? (int64_t)ks * M * N * 4 : 0;
 }

@@ -428,6 +428,191 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     }
 }
 
+// ---- NVFP4, register-direct, small tiles: prefill chunks of 64 .. 1024 tokens -------------------
+
+// With a few hundred tokens the 128x128 wave tiles above are too few to occupy the chip, and the
+// time of a layer is launch latency plus one trip of the weights from HBM.  Here a workgroup owns
+// one (32 TM) x (32 TN) output tile; its S waves (S chosen at launch, S <= MAXS) take consecutive
+// parts of K and each runs the same register-direct K loop as above (operands loaded in MFMA
+// order, expanded in registers, no LDS and no barrier in the loop) with NSETS K steps of codes in
+// flight per wave.  The S partial tiles are then added through LDS in a fixed order (wave 0, 1,
+// ...: bit-identical from run to run), each wave summing, scaling, rounding and storing 1/S of the
+// tile.  No workspace and no second kernel: one launch per layer.  Smaller wave tiles raise the
+// conversion work per MFMA (TM + TN operand tiles expanded for TM x TN MFMAs: 8 VALU instructions
+// per MFMA for 64x64, 6 for 128x64) but multiply the number of waves that pull on memory.
+template <int TM_, int TN_>
+struct SmallCfg {
+    static constexpr int TM = TM_, TN = TN_, WN = 32 * TN_;
+};
+
+template <int TM, int TN, int MAXS, int NSETS, bool OUT_BF16>
+__global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tiles_m, int tiles_n)
+{
+    constexpr int NT = TM + TN;
+    static_assert((TM * TN) % 4 == 0 || TM * TN < 4, "the LDS reduction moves four 32x32 tiles per pass");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int S = (int)(blockDim.x >> 6);  // waves that share this tile's K range
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int KT = (int)(g.K / BK);
+    const int KH = (KT + S - 1) / S;
+    const int k0 = wave * KH < KT ? wave * KH : KT;
+    const int k1 = k0 + KH < KT ? k0 + KH : KT;
+    // tiles that share a column panel of B are neighbours in the tile order and run on one XCD
+    const int t = logical_id(blockIdx.x, tiles_m * tiles_n);
+    const int tm = t % tiles_m, tn = t / tiles_m;
+    const int64_t m0 = (int64_t)tm * (32 * TM), n0 = (int64_t)tn * (32 * TN);  // m0 < M, n0 < N
+
+    // operand q: A row tile q (q < TM), else B row tile q - TM.  Lane offsets relative to the tile.
+    const char *const ta_c = static_cast<const char *>(g.a) + m0 * g.a_c_row;
+    const char *const tb_c = static_cast<const char *>(g.b) + n0 * g.b_c_row;
+    const char *const ta_s = reinterpret_cast<const char *>(g.a_scales) + m0 * g.a_s_row;
+    const char *const tb_s = reinterpret_cast<const char *>(g.b_scales) + n0 * g.b_s_row;
+    uint32_t vc[NT], vs[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+        const bool isA = q < TM;
+        const int64_t total = isA ? g.M : g.N, first = isA ? m0 : n0;
+        int64_t grow = first + (isA ? q : q - TM) * 32 + frow;
+        grow = grow < total ? grow : total - 1;
+        vc[q] = (uint32_t)((grow - first) * (isA ? g.a_c_row : g.b_c_row) + fhalf * 16);
+        vs[q] = (uint32_t)((grow - first) * (isA ? g.a_s_row : g.b_s_row));
+    }
+    uint4 rc[NSETS][NT];     // this lane's 32 codes of each operand tile, NSETS K steps
+    uint32_t rs[NSETS][NT];  // the rows' four E4M3 scale bytes
+    auto load_step = [&](int kt, auto setc) {
+        constexpr int R = decltype(setc)::value;
+        kt = kt < KT ? kt : KT - 1;
+        auto rsrc = [](const char *base, int64_t off) {
+            return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base) + off, 0, -1, 0x00020000);
+        };
+        const __amdgpu_buffer_rsrc_t rac = rsrc(ta_c, (int64_t)kt * g.a_c_step), rbc = rsrc(tb_c, (int64_t)kt * g.b_c_step);
+        const __amdgpu_buffer_rsrc_t ras = rsrc(ta_s, (int64_t)kt * g.a_s_step), rbs = rsrc(tb_s, (int64_t)kt * g.b_s_step);
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < TM ? rac : rbc, (int)vc[q], 0, 0);
+            rc[R][q] = make_uint4(c[0], c[1], c[2], c[3]);
+            rs[R][q] = __builtin_amdgcn_raw_buffer_load_b32(q < TM ? ras : rbs, (int)vs[q], 0, 0);
+        }
+    };
+    // scales, expansion and MFMAs exactly as in gemm_fp4_direct (K index of a lane: 32h + 8p + j)
+    uint32_t sg[NT];
+    const uint32_t sel_valid = 0x0C000C00u | (uint32_t)(2 * fhalf) | ((uint32_t)(2 * fhalf + 1) << 16);
+    auto prep_scales = [&](auto setc, bool valid) {
+        constexpr int R = decltype(setc)::value;
+        const uint32_t sel = valid ? sel_valid : 0x0C0C0C0Cu;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            uint32_t sc = rs[R][q];
+            asm volatile("" : "+v"(sc));
+            sg[q] = __builtin_amdgcn_perm(0u, sc, sel) << 7;
+        }
+    };
+    uint4 fr[2][NT];
+    auto expand_phase = [&](auto setc, int p, uint4(&f)[NT]) {
+        constexpr int R = decltype(setc)::value;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            uint32_t w = p == 0 ? rc[R][q].x : p == 1 ? rc[R][q].y : p == 2 ? rc[R][q].z : rc[R][q].w;
+            asm volatile("" : "+v"(w));
+            const _Float16 sig = __builtin_bit_cast(_Float16, (uint16_t)(p < 2 ? sg[q] : sg[q] >> 16));
+            const f16x2 sv = {sig, sig};
+            f16x2 c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 0);
+            f16x2 c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 1);
+            f16x2 c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 2);
+            f16x2 c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 3);
+            asm volatile("" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
+            c0 *= sv, c1 *= sv, c2 *= sv, c3 *= sv;
+            f[q] = make_uint4(__builtin_bit_cast(uint32_t, c0), __builtin_bit_cast(uint32_t, c1),
+                              __builtin_bit_cast(uint32_t, c2), __builtin_bit_cast(uint32_t, c3));
+        }
+    };
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+    auto mfmas = [&](const uint4(&f)[NT]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    __builtin_bit_cast(f16x8, f[i]), __builtin_bit_cast(f16x8, f[TM + j]), acc[i][j], 0, 0, 0);
+    };
+    constexpr int NM = TM * TN, VPER = (NT * 8 + NM - 1) / NM;
+    auto kstep = [&](int kt, auto setc) {
+        constexpr int R = decltype(setc)::value;
+        using Next = std::integral_constant<int, (R + 1) % NSETS>;
+        expand_phase(setc, 1, fr[1]);
+        mfmas(fr[0]);
+        sched_phase<NM, 0, VPER, 0, 0>();
+        expand_phase(setc, 2, fr[0]);
+        mfmas(fr[1]);
+        sched_phase<NM, 0, VPER, 0, 0>();
+        expand_phase(setc, 3, fr[1]);
+        mfmas(fr[0]);
+        sched_phase<NM, 0, VPER, 0, 0>();
+        prep_scales(Next{}, kt + 1 < k1);
+        expand_phase(Next{}, 0, fr[0]);
+        load_step(kt + NSETS, setc);
+        mfmas(fr[1]);
+        sched_phase<NM, 0, VPER + 2, 0, (2 * NT + NM - 1) / NM>();
+    };
+    auto for_sets = [&](auto &&fn) {  // fn(set index as a constant), sets 0 .. NSETS-1
+        fn(std::integral_constant<int, 0>{});
+        if constexpr (NSETS > 1) fn(std::integral_constant<int, 1>{});
+        if constexpr (NSETS > 2) fn(std::integral_constant<int, 2>{});
+        if constexpr (NSETS > 3) fn(std::integral_constant<int, 3>{});
+    };
+    static_assert(NSETS >= 1 && NSETS <= 4, "one to four K steps in flight");
+    for_sets([&](auto u) { load_step(k0 + decltype(u)::value, u); });
+    const float scale = (*g.a_alpha) * (*g.b_alpha);
+    prep_scales(std::integral_constant<int, 0>{}, k0 < k1);
+    expand_phase(std::integral_constant<int, 0>{}, 0, fr[0]);
+    // whole groups of NSETS K steps; a step past the end multiplies by zero scales
+    for (int kt = k0; kt < k1; kt += NSETS) for_sets([&](auto u) { kstep(kt + decltype(u)::value, u); });
+
+    if (S == 1) {
+        epilogue<SmallCfg<TM, TN>, OUT_BF16>(g, acc, scale, m0, n0, 0, 0, frow, fhalf);
+        return;
+    }
+    // Sum over the S waves through LDS, four 32x32 tiles (16 KB per wave) per pass.  A pass holds 16
+    // chunks of four accumulator registers per wave; wave w adds the S copies of chunks w, w + S,
+    // ... in wave order and stores them: chunk c of a tile = rows 8c + 4 (lane / 32) .. + 3.
+    extern __shared__ uint4 lds[];
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4 *const X = reinterpret_cast<f32x4 *>(lds);
+    using T = std::conditional_t<OUT_BF16, __bf16, float>;
+    constexpr int PASS = NM < 4 ? NM : 4;  // tiles per pass
+#pragma unroll
+    for (int p0 = 0; p0 < NM; p0 += PASS) {
+        if (p0 > 0) __syncthreads();  // the previous pass has been read
+#pragma unroll
+        for (int u = 0; u < PASS; ++u) {
+            const f32x16 &tl = acc[(p0 + u) / TN][(p0 + u) % TN];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                X[((wave * PASS + u) * 4 + c) * 64 + lane] = f32x4{tl[4 * c], tl[4 * c + 1], tl[4 * c + 2], tl[4 * c + 3]};
+        }
+        __syncthreads();
+        for (int ch = wave; ch < PASS * 4; ch += S) {
+            f32x4 sum = X[ch * 64 + lane];
+            for (int w = 1; w < S; ++w) sum += X[(w * PASS * 4 + ch) * 64 + lane];
+            const int tile = p0 + (ch >> 2), c = ch & 3;
+            const int64_t n = n0 + (tile % TN) * 32 + frow;
+            const int64_t mrow = m0 + (tile / TN) * 32 + 8 * c + 4 * fhalf;
+            if (n < g.N) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (mrow + e < g.M) static_cast<T *>(g.y)[(mrow + e) * g.ldy + n] = (T)(sum[e] * scale);
+            }
+        }
+    }
+}
+
 // Second pass of the slab-split product: y[m][n] = round(scale * (ws[0][m][n] + ws[1][m][n] + ...)),
 // slabs added in ascending order.  One thread per four consecutive columns (N % 4 == 0 here).
 template <bool OUT_BF16>
@@ -968,6 +1153,19 @@ int launch_persistent(Kern kern, int bm, int bn, size_t lds_bytes, const GemmArg
     return note_launch(hipGetLastError());
 }
 
+// One workgroup of S waves per (32 TM) x (32 TN) tile.
+template <int TM, int TN, int MAXS, int NSETS, bool OUT_BF16>
+int launch_small(const GemmArgs &g, hipStream_t s, int S)
+{
+    const int64_t tiles_m = (g.M + 32 * TM - 1) / (32 * TM), tiles_n = (g.N + 32 * TN - 1) / (32 * TN);
+    if (tiles_m * tiles_n > 0x7FFFFFFF || S < 1 || S > MAXS) return MQ_ERR_SHAPE;
+    constexpr int PASS = TM * TN < 4 ? TM * TN : 4;
+    const size_t lds = S > 1 ? (size_t)S * PASS * 4096 : 0;
+    gemm_fp4_small<TM, TN, MAXS, NSETS, OUT_BF16>
+        <<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * S), lds, s>>>(g, (int)tiles_m, (int)tiles_n);
+    return note_launch(hipGetLastError());
+}
+
 template <bool FP4, bool OUT_BF16>
 int launch_simple(const GemmArgs &g, hipStream_t s)
 {
@@ -1022,6 +1220,10 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         // being charged 55 / 34 percent of a whole one (measured on M = 512 .. 8192).
         int cus = 0;
         if (int rc = compute_units(cus)) return rc;
+        // A few hundred tokens: 64x64 tiles with K split over the waves of a workgroup, one launch
+        // (or, for a long K with very few tiles and a workspace, slabs of K across workgroups).
+        const int sw = gemm_fp4_small_waves(g.M, g.N, g.K, g.ws ? g.ws_bytes : 0, cus);
+        if (sw > 0) return launch_small<2, 2, 8, 4, OUT_BF16>(g, s, sw);
         const int64_t small_tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
         const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus,
                       r4 = (small_tiles + cus - 1) / cus;
@@ -1087,10 +1289,30 @@ int configure_gemm_kernels()
     both(gemm_fp4_direct<true, 2>, gemm_fp4_direct<false, 2>, X);
     both(gemm_fp4_direct<true, 4>, gemm_fp4_direct<false, 4>, X);
     both(gemm_fp4_direct<true, 4, true>, gemm_fp4_direct<false, 4, true>, X);
+    both(gemm_fp4_small<2, 2, 8, 4, true>, gemm_fp4_small<2, 2, 8, 4, false>, X);
     both(gemm_bf16_d2l<D, true>, gemm_bf16_d2l<D, false>, D::LDS_BYTES);
     both(gemm_bf16_d2l<Mid, true>, gemm_bf16_d2l<Mid, false>, Mid::LDS_BYTES);
     both(gemm_bf16_pipelined<Small, true>, gemm_bf16_pipelined<Small, false>, Small::LDS_BYTES);
     return note_launch(e);
+}
+
+// Waves per 64x64 tile if the small-tile kernel serves this problem, else 0.  Measured on the
+// Llama-3-8B layer set at 64 .. 1024 tokens (one GPU, times of one launch inside a HIP graph): up
+// to 2 x CUs tiles of 64x64 it beats the 128x128 wave tiles (M = 128, N = 4096, K = 4096: 10.9 us
+// against 19.2 with slabs and 27 without), beyond that the larger tiles' lower conversion work
+// per MFMA wins.  Eight waves per tile (two per SIMD) while every tile gets a compute unit of
+// its own, four beyond.  Exception: a long K with very few tiles and a workspace at hand, where
+// slabs of K across workgroups occupy more compute units (M = 64, N = 4096, K = 14336: 23.6 us
+// against 25.5).
+int gemm_fp4_small_waves(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
+{
+    if (M <= 0 || N <= 0 || K % BK != 0) return 0;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64), kt = K / BK;
+    if (tiles > 2 * (int64_t)cus) return 0;
+    if (2 * tiles <= cus && kt >= 128 && gemm_fp4_ksplit(M, N, K, ws_bytes, cus) >= 2) return 0;
+    int64_t waves = tiles <= cus ? 8 : 4;
+    if (waves > kt / 2) waves = kt / 2 > 0 ? kt / 2 : 1;  // at least two K steps per wave
+    return (int)waves;
 }
 
 int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)

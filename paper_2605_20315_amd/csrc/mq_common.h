@@ -62,6 +62,8 @@ struct GemmArgs {
 };
 // K slabs the NVFP4 launcher would cut a problem into (1: none), given this much workspace
 int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
+// waves per 64x64 tile if the small-tile NVFP4 kernel serves this problem (given this much workspace), else 0
+int gemm_fp4_small_waves(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
 // sets the dynamic-LDS limit of every tiled kernel on the current device (idempotent)
 int configure_gemm_kernels();
 int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);

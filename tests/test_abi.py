@@ -85,17 +85,18 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
 
 
 def test_workspace_size_query(lib):
-    """Host-only: slabs are offered for problems with fewer than 64 output tiles of 128x128 whose K
-    is long enough, the size is slabs * M * N * 4 bytes and never exceeds one 128x128 FP32 tile per
-    compute unit of the largest gfx950 part (256 x 64 KiB)."""
+    """Host-only: slabs of K across workgroups are offered only for a long K (at least 128 K steps)
+    with at most 128 output tiles of 64x64; the size is slabs * M * N * 4 bytes and never exceeds
+    one 128x128 FP32 tile per compute unit of the largest gfx950 part (256 x 64 KiB)."""
     q = lib.mq_gemm_workspace_bytes
-    assert q(8192, 4096, 4096) == 0          # 2048 tiles
-    assert q(128, 28672, 4096) == 0          # 224 tiles
-    assert q(128, 4096, 448) == 0            # 7 K steps: nothing to cut
-    assert q(128, 4098, 4096) == 0           # N % 4 != 0
-    assert q(128, 4096, 4080) == 0           # K % 64 != 0
+    assert q(8192, 4096, 4096) == 0          # 2048 tiles of 128x128
+    assert q(128, 28672, 4096) == 0          # 896 tiles of 64x64
+    assert q(128, 4096, 4096) == 0           # 64 K steps: the one-launch small-tile kernel
+    assert q(256, 4096, 14336) == 0          # 256 tiles of 64x64: small-tile kernel
+    assert q(128, 4098, 14336) == 0          # N % 4 != 0
+    assert q(128, 4096, 14320) == 0          # K % 64 != 0
     assert q(0, 4096, 4096) == 0 and q(128, 0, 4096) == 0 and q(128, 4096, 0) == 0
-    for M, N, K in [(128, 4096, 4096), (64, 4096, 14336), (300, 1024, 8192), (17, 136, 65536)]:
+    for M, N, K in [(128, 4096, 14336), (64, 4096, 14336), (300, 1024, 8192), (17, 136, 65536)]:
         b = q(M, N, K)
         assert b > 0 and b % (M * N * 4) == 0
         slabs = b // (M * N * 4)

@@ -32,12 +32,14 @@ def _reference(ac, asc, aa, bc, bsc, ba):
     return oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b)
 
 
-# (M, N, K): K / 64 K steps; with 256 compute units the launcher picks up to min(256 / tiles, K / 512)
-# slabs.  (100, 520, 4096): 5 tiles, 8 slabs; (128, 4096, 14336): 32 tiles, 7 slabs, 224 K steps
-# do not divide evenly; (300, 264, 1024): 9 tiles, 2 slabs; (64, 1032, 1536): 3 slabs of 8 steps;
-# (17, 136, 8192): 2 tiles, 16 slabs; (130, 2048, 1088): 17 K steps, slabs with idle waves.
-SHAPES = [(100, 520, 4096), (128, 4096, 14336), (300, 264, 1024), (64, 1032, 1536), (17, 136, 8192),
-          (130, 2048, 1088), (1, 8, 1024)]
+# (M, N, K).  Slabs of K across workgroups (with a workspace) need K >= 8192 and at most 128 tiles
+# of 64x64; with 256 compute units the launcher picks up to min(256 / tiles of 128x128, K / 512)
+# of them.  (100, 520, 8192): 5 tiles, 8 slabs; (128, 4096, 14336): 32 tiles, 7 slabs, 224 K steps
+# do not divide evenly; (300, 264, 8192): 9 tiles; (64, 1032, 12288): odd N tail; (17, 136, 8192):
+# 2 tiles, 16 slabs; (130, 2048, 8256): 129 K steps, slabs with idle waves.  The shapes with a
+# shorter K take the one-launch small-tile kernel with or without a workspace.
+SHAPES = [(100, 520, 8192), (128, 4096, 14336), (300, 264, 8192), (64, 1032, 12288), (17, 136, 8192),
+          (130, 2048, 8256), (1, 8, 8192), (100, 520, 4096), (300, 264, 1024), (64, 1032, 1536), (1, 8, 1024)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -51,6 +53,7 @@ def test_small_m_with_and_without_workspace(M, N, K, layout):
     a_al, b_al = dev_scalar(aa), dev_scalar(ba)
     need = mq.mq_gemm_workspace_bytes(M, N, K)
     assert 0 <= need <= 16 << 20
+    assert (need > 0) == (K >= 8192)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     got = {}
     for out in (mq.MQ_OUT_BF16, mq.MQ_OUT_FP32):
@@ -86,8 +89,8 @@ def test_workspace_size_limits_the_slabs_and_odd_n_uses_none():
         torch.cuda.synchronize()
         check_gemm_fp32(y.cpu().numpy(), ref, na, nb)
     # N % 4 != 0: the second pass works on groups of four columns, so no slabs; the result must be right
-    M, N, K = 40, 1030, 2048
-    assert mq.mq_gemm_workspace_bytes(M, N, K) == 0
+    M, N, K = 40, 1030, 8192
+    assert mq.mq_gemm_workspace_bytes(M, N, K) == 0 and mq.mq_gemm_workspace_bytes(M, N + 2, K) > 0
     ops = _operands(M, N, K, 2)
     ref, na, nb = _reference(*ops)
     ac, asc, aa, bc, bsc, ba = ops
@@ -103,7 +106,7 @@ def test_workspace_size_limits_the_slabs_and_odd_n_uses_none():
 
 
 def test_slabs_into_a_column_slice_and_workspace_argument_checks():
-    M, N, K = 120, 520, 4096
+    M, N, K = 120, 520, 8192
     ops = _operands(M, N, K, 3)
     ref, na, nb = _reference(*ops)
     ac, asc, aa, bc, bsc, ba = ops
@@ -138,7 +141,7 @@ def test_slab_split_chain_replays_from_a_hip_graph():
     from paper_2605_20315_amd import workloads as wl
     from _gpu_util import dev_bf16
     rng = np.random.default_rng(79)
-    M, K, N = 96, 4096, 2048
+    M, K, N = 96, 8192, 2048
     mk = lambda: dev_bf16(wl.f32_to_bf16_bits((rng.standard_normal((M, K)) * rng.uniform(0.5, 4.0)).astype(np.float32)))
     w = dev_bf16(wl.f32_to_bf16_bits((rng.standard_normal((N, K)) * K ** -0.5).astype(np.float32)))
     aw = mq.nvfp4_global_scale(w)
