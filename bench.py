@@ -7,20 +7,24 @@ the BF16 activations to NVFP4 on the fly (nvfp4_quantize) and run the block-scal
 the offline-quantized weights (nvfp4_gemm_ws, BF16 out).  Inputs are resident in HBM before the
 timed region; tensor-level scales and weight quantization are computed once, untimed.
 
-Prints ONE JSON line.  `value` = 2*M*N*K summed over the four layers / step time, in TFLOP/s.
-Also measured: the dominant kernel's (NVFP4 GEMM) average launch duration with HIP events on
-the launch stream (-> roofline), the quantizer's bandwidth, the in-repo BF16 GEMM on the same
-shapes (-> speed-up), and the CPU oracle on a bounded sample (-> cpu_baseline).  Further lines of
-the same JSON object, all outside the timed region: the vendor library's BF16 GEMM as context,
-the dynamic-alpha pipeline, decode-shape weight streaming, the producer-fused quantizers and
-the MLP block as a dependent chain, a tokens-per-batch sweep (64 .. 131072), and the rate an
-MFMA-only loop sustains on this machine.
+Prints ONE JSON line.  `value` = 2*M*N*K summed over the four layers / mean step time (wall clock
+over exactly --steps steps between two synchronisations), in TFLOP/s; the median and the fastest
+step (HIP events around every step) are reported beside it.  Also measured: the dominant kernel's
+(NVFP4 GEMM) average launch duration with HIP events on the launch stream (-> roofline), the
+quantizer's bandwidth, the in-repo BF16 GEMM and the vendor library's on the same shapes
+(-> speed-ups), and the CPU oracle on a bounded sample (-> cpu_baseline).  Further members of the
+same JSON object, all outside the timed region: the other four workload configurations, the
+dynamic-alpha pipeline, decode-shape weight streaming, the producer-fused quantizers and the MLP
+block as a dependent chain, a tokens-per-batch sweep (64 .. 131072), and the rate an MFMA-only
+loop sustains on this machine.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -32,6 +36,23 @@ PEAK_MFMA_16BIT = 2516.6
 PEAK_MFMA_FP4 = 10066.3
 PEAK_HBM_GBS = 8000.0
 QUANT_BYTES_PER_ELT = 2.0 + 0.5 + 1.0 / 16.0   # BF16 in, 4-bit code + 1/16 scale byte out
+# rocprofv3 summary of this command; its "bench.roofline.*" lines feed roofline.traffic / kernel
+PROFILE_SUMMARY = os.path.join(ROOT, "profiles", "nvfp4_gemm_bf16_gemm_quantizer_llama8b_m8192.md")
+
+
+def profile_facts(path: str) -> dict:
+    """`bench.roofline.<key> = <value>` lines of the tracked rocprofv3 summary (measured HBM bytes
+    per launch of the dominant kernel and its name); empty when the summary is missing."""
+    facts = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                m = re.match(r"\s*bench\.roofline\.(\w+)\s*=\s*(.+?)\s*$", line)
+                if m:
+                    facts[m.group(1)] = m.group(2).strip("`")
+    except OSError:
+        pass
+    return facts
 
 
 def main() -> int:
@@ -44,6 +65,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample-rows", type=int, default=4096)
     ap.add_argument("--no-sweep", action="store_true", help="skip the tokens-per-batch sweep (second workload)")
     ap.add_argument("--no-fused", action="store_true", help="skip the producer-fused quantizers and the MLP chain")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other four workload configurations")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -62,15 +84,52 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    mq.mq_init()
     cfg = wl.configs()[args.config]
     M = cfg.M
     LAYOUT = mq.MQ_LAYOUT_KTILE     # K-step-major NVFP4 bytes: the layout the GEMM streams
-    # caller-owned workspace of the NVFP4 product (used only below about 512 tokens, where K is
-    # cut into slabs across workgroups); the library's largest request is 16 MiB
+    # caller-owned workspace of the NVFP4 product (used only for a long K with very few output
+    # tiles, where K is cut into slabs across workgroups); the library's largest request is 16 MiB
     GEMM_WS = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    def event():
+        return torch.cuda.Event(enable_timing=True)
+
+    def gpu_ms(fn, reps, warm=2, graph=False):
+        """Mean time of fn() in ms over `reps` back-to-back calls, by HIP events on the launch stream.
+        graph=True: the reps are captured into one HIP graph and replayed (what a serving loop does
+        for launches of a few microseconds, where the host cannot keep up with the GPU)."""
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        if graph:
+            try:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for _ in range(reps):
+                        fn()
+                g.replay()
+                torch.cuda.synchronize()
+                e0, e1 = event(), event()
+                e0.record()
+                for _ in range(3):
+                    g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / (3 * reps)
+            except Exception as exc:    # capture refused (a library call that allocates): time it eagerly
+                print(f"bench.py: graph capture skipped: {exc}", file=sys.stderr)
+                torch.cuda.synchronize()
+        e0, e1 = event(), event()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
 
     # ---- inputs resident in HBM, weights quantized offline, scales calibrated once (untimed) ----
     layers = []
@@ -92,7 +151,7 @@ def main() -> int:
     def step(events=None):
         for L in layers:
             if events is not None:
-                e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                e = [event() for _ in range(3)]
                 e[0].record()
             mq.nvfp4_quantize(L["x"], L["ax"], L["xc"], L["xs"], LAYOUT)
             if events is not None:
@@ -110,6 +169,7 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- the timed region: exactly --steps steps between two synchronisations ----
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -128,6 +188,8 @@ def main() -> int:
     for i, e in enumerate(events):
         q_ms[i % nl] += e[0].elapsed_time(e[1]) / args.steps
         g_ms[i % nl] += e[1].elapsed_time(e[2]) / args.steps
+    # one step = from the first event of its first layer to the last event of its last layer
+    step_ms = [events[s * nl][0].elapsed_time(events[s * nl + nl - 1][2]) for s in range(args.steps)]
     gemm_ms_step, quant_ms_step = sum(g_ms), sum(q_ms)
     gemm_tflops = flop_step / (gemm_ms_step * 1e-3) * 1e-12
     quant_gbs = quant_bytes_step / (quant_ms_step * 1e-3) * 1e-9
@@ -140,87 +202,127 @@ def main() -> int:
             mq.nvfp4_gemm_ws(L["xc"], L["xs"], L["ax_dyn"], L["wc"], L["ws"], L["aw"], GEMM_WS, mq.MQ_OUT_BF16, L["y"], LAYOUT)
     for L in layers:
         L["ax_dyn"] = torch.empty(1, dtype=torch.float32, device="cuda")
-    for _ in range(max(1, args.warmup // 2)):
-        dyn_step()
-    torch.cuda.synchronize()
-    d0 = time.perf_counter()
     nd = max(3, args.steps // 2)
-    for _ in range(nd):
-        dyn_step()
-    torch.cuda.synchronize()
-    dyn_ms_step = (time.perf_counter() - d0) * 1e3 / nd
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(10):
+    dyn_ms_step = gpu_ms(dyn_step, nd, max(1, args.warmup // 2))
+
+    def amax_all():
         for L in layers:
             mq.nvfp4_global_scale(L["x"], L["ax_dyn"])
-    e1.record()
-    torch.cuda.synchronize()
-    amax_gbs = 10 * sum(2.0 * M * L["layer"].K for L in layers) / (e0.elapsed_time(e1) * 1e-3) * 1e-9
+    amax_gbs = sum(2.0 * M * L["layer"].K for L in layers) / (gpu_ms(amax_all, 10) * 1e-3) * 1e-9
 
     # ---- BF16 GEMM on the same shapes (the high-precision baseline) ----
     def bf16_step():
         for L in layers:
             mq.bf16_gemm(L["x"], L["w"], mq.MQ_OUT_BF16, L["y"])
-    for _ in range(max(1, args.warmup // 2)):
-        bf16_step()
-    torch.cuda.synchronize()
-    b0 = time.perf_counter()
     nb = max(3, args.steps // 2)
-    for _ in range(nb):
-        bf16_step()
-    torch.cuda.synchronize()
-    bf16_ms_step = (time.perf_counter() - b0) * 1e3 / nb
+    bf16_ms_step = gpu_ms(bf16_step, nb, max(1, args.warmup // 2))
     bf16_tflops = flop_step / (bf16_ms_step * 1e-3) * 1e-12
 
     # ---- context: the vendor library's BF16 GEMM (hipBLASLt through torch.matmul) on the same shapes ----
-    lib_tflops = None
+    lib_ms_step = None
     try:
         def lib_step():
             for L in layers:
                 torch.matmul(L["x"], L["w"].t(), out=L["y"])
-        for _ in range(3):
-            lib_step()
-        torch.cuda.synchronize()
-        l0 = time.perf_counter()
-        for _ in range(nb):
-            lib_step()
-        torch.cuda.synchronize()
-        lib_tflops = flop_step / ((time.perf_counter() - l0) / nb) * 1e-12
+        lib_ms_step = gpu_ms(lib_step, nb, 3)
     except Exception as exc:  # the library path is context only; never fail the run on it
         print(f"bench.py: torch.matmul reference skipped: {exc}", file=sys.stderr)
+    lib_tflops = None if lib_ms_step is None else flop_step / (lib_ms_step * 1e-3) * 1e-12
 
     # ---- decode shapes of the high-precision path: a few tokens against the same weights (HBM-bound) ----
     decode = {}
     w_bytes = sum(2.0 * L["layer"].N * L["layer"].K for L in layers)
-    for md in (1, 16, 64):
+    for md in (1, 16, 32, 64):
         def dec_step():
             for L in layers:
                 mq.bf16_gemm(L["x"][:md], L["w"], mq.MQ_OUT_BF16, L["y"][:md])
-        for _ in range(3):
-            dec_step()
-        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        g0.record()
-        for _ in range(20):
-            dec_step()
-        g1.record()
-        torch.cuda.synchronize()
-        decode[f"M={md}"] = round(20 * w_bytes / (g0.elapsed_time(g1) * 1e-3) * 1e-9, 1)
+        decode[f"M={md}"] = round(w_bytes / (gpu_ms(dec_step, 20, 3, graph=True) * 1e-3) * 1e-9, 1)
+
+    # ---- one configuration's layer set on device-resident tensors: quantizer, GEMM, both, baselines ----
+    def measure_layer_set(mm, specs, reps, graph):
+        """specs: list of (name, K, N, x, w).  Returns the compact record of one configuration."""
+        tq = tg = tqg = tb = tv = 0.0
+        flop = qbytes = 0.0
+        for name, K, N, x, w in specs:
+            ax, aw = mq.nvfp4_global_scale(x), mq.nvfp4_global_scale(w)
+            wc, ws = mq.nvfp4_quantize(w, aw, layout=LAYOUT)
+            xc = torch.empty((mm, K // 2), dtype=torch.uint8, device="cuda")
+            xs = torch.empty((mm, K // 16), dtype=torch.uint8, device="cuda")
+            y = torch.empty((mm, N), dtype=torch.bfloat16, device="cuda")
+
+            def quant():
+                mq.nvfp4_quantize(x, ax, xc, xs, LAYOUT)
+
+            def gemm():
+                mq.nvfp4_gemm_ws(xc, xs, ax, wc, ws, aw, GEMM_WS, mq.MQ_OUT_BF16, y, LAYOUT)
+
+            def both():
+                quant()
+                gemm()
+            tq += gpu_ms(quant, reps, 2, graph)
+            tg += gpu_ms(gemm, reps, 2, graph)
+            tqg += gpu_ms(both, reps, 2, graph)
+            tb += gpu_ms(lambda: mq.bf16_gemm(x, w, mq.MQ_OUT_BF16, y), reps, 2, graph)
+            tv += gpu_ms(lambda: torch.matmul(x, w.t(), out=y), reps, 2, graph)
+            flop += 2.0 * mm * N * K
+            qbytes += QUANT_BYTES_PER_ELT * mm * K
+            del xc, xs, y, wc, ws
+        tf = lambda t: round(flop / (t * 1e-3) * 1e-12, 1)
+        return {"M": mm, "quantizer_gbs": round(qbytes / (tq * 1e-3) * 1e-9, 1), "gemm_only_tflops": tf(tg),
+                "quant_plus_gemm_tflops": tf(tqg), "quant_plus_gemm_us": round(tqg * 1e3, 1),
+                "bf16_gemm_tflops": tf(tb), "vendor_library_bf16_gemm_tflops": tf(tv),
+                "x_vs_bf16_gemm": round(tb / tqg, 3), "x_vs_vendor_library_bf16_gemm": round(tv / tqg, 3)}
+
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+
+    def device_activation(c, layer, mm):
+        """The workload recipe evaluated on the device (the host generator of workloads.py is the
+        definition; tensors of 10^9 elements take it minutes): N(0,1), Student-t(4) for the down
+        input where the configuration says so, per-token lognormal magnitudes for the 32B-class
+        configuration, 0.1 % of the channels scaled by the outlier gain."""
+        K = layer.K
+        x = torch.randn((mm, K), dtype=torch.float32, device="cuda", generator=gen)
+        if c.student_t_down and layer.name == "down":
+            chi = torch.zeros((mm, K), dtype=torch.float32, device="cuda")
+            for _ in range(4):
+                chi += torch.randn((mm, K), dtype=torch.float32, device="cuda", generator=gen) ** 2
+            x /= torch.sqrt(chi / 4.0)
+            del chi
+        if c.token_lognormal:
+            x *= torch.exp(torch.randn((mm, 1), dtype=torch.float32, device="cuda", generator=gen))
+        n_out = c.outlier_count if c.outlier_frac == 0 else max(1, round(c.outlier_frac * K))
+        cols = torch.randperm(K, device="cuda", generator=gen)[:n_out]
+        x[:, cols] *= c.outlier_gain
+        return x.to(torch.bfloat16)
+
+    def device_weight(c, layer):
+        std = c.weight_std if c.weight_std > 0 else layer.K ** -0.5
+        return (torch.randn((layer.N, layer.K), dtype=torch.float32, device="cuda", generator=gen) * std).to(torch.bfloat16)
+
+    # ---- the other workload configurations (tiny, M = 2048, 32B-class M = 16384, ragged M = 108351) ----
+    other_configs = None
+    if args.config == 2 and not args.no_configs:
+        other_configs = {}
+        for c in wl.configs():
+            if c.cfg_id == args.config:
+                continue
+            specs = []
+            for layer in c.layers:
+                same = next((L for L in layers if (L["layer"].K, L["layer"].N) == (layer.K, layer.N)), None)
+                w = same["w"] if same is not None and c.weight_std == 0 else device_weight(c, layer)
+                specs.append((layer.name, layer.K, layer.N, device_activation(c, layer, c.M), w))
+            small = c.M <= 2048
+            rec = measure_layer_set(c.M, specs, 20 if small else 3, small)
+            rec["data"] = "recipe of workloads.py evaluated on the device (seeded torch generator)"
+            other_configs[c.name] = rec
+            del specs
+            torch.cuda.empty_cache()
 
     # ---- producer-fused quantizers (the quantizer fused with its neighbour, Section 3.3): the two
     # activations of a decoder block that are quantized, against producer (torch) + nvfp4_quantize ----
     fused = None
     if args.config == 2 and not args.no_fused:
-        def timed(fn, reps=20):
-            for _ in range(3):
-                fn()
-            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            f0.record()
-            for _ in range(reps):
-                fn()
-            f1.record()
-            torch.cuda.synchronize()
-            return f0.elapsed_time(f1) / reps
         Kd, Kh = 14336, 4096
         gu = torch.randn((M, 2 * Kd), dtype=torch.bfloat16, device="cuda")
         xh = torch.randn((M, Kh), dtype=torch.bfloat16, device="cuda")
@@ -230,10 +332,10 @@ def main() -> int:
         sd = torch.empty((M, Kd // 16), dtype=torch.uint8, device="cuda")
         ch = torch.empty((M, Kh // 2), dtype=torch.uint8, device="cuda")
         sh = torch.empty((M, Kh // 16), dtype=torch.uint8, device="cuda")
-        t_f1 = timed(lambda: mq.nvfp4_quantize_silu_mul(gu, a1, cd, sd, LAYOUT))
-        t_u1 = timed(lambda: mq.nvfp4_quantize(torch.nn.functional.silu(gu[:, :Kd]) * gu[:, Kd:], a1, cd, sd, LAYOUT))
-        t_f2 = timed(lambda: mq.nvfp4_quantize_rmsnorm(xh, gw, 1e-6, a1, ch, sh, LAYOUT))
-        t_u2 = timed(lambda: mq.nvfp4_quantize(torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6), a1, ch, sh, LAYOUT))
+        t_f1 = gpu_ms(lambda: mq.nvfp4_quantize_silu_mul(gu, a1, cd, sd, LAYOUT), 20, 3)
+        t_u1 = gpu_ms(lambda: mq.nvfp4_quantize(torch.nn.functional.silu(gu[:, :Kd]) * gu[:, Kd:], a1, cd, sd, LAYOUT), 20, 3)
+        t_f2 = gpu_ms(lambda: mq.nvfp4_quantize_rmsnorm(xh, gw, 1e-6, a1, ch, sh, LAYOUT), 20, 3)
+        t_u2 = gpu_ms(lambda: mq.nvfp4_quantize(torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6), a1, ch, sh, LAYOUT), 20, 3)
         fused = {
             "silu_mul_quantize": {"shape": [M, Kd], "fused_ms": round(t_f1, 4), "producer_then_quantize_ms": round(t_u1, 4),
                                   "fused_gbs": round((4.0 + QUANT_BYTES_PER_ELT - 2.0) * M * Kd / (t_f1 * 1e-3) * 1e-9, 1)},
@@ -259,85 +361,53 @@ def main() -> int:
             mq.nvfp4_quantize_silu_mul(yg, a_p, cd, sd, LAYOUT)
             mq.nvfp4_gemm_ws(cd, sd, a_p, Ld["wc"], Ld["ws"], Ld["aw"], GEMM_WS, mq.MQ_OUT_BF16, yo, LAYOUT)
 
-        def mlp_bf16():
+        def mlp_bf16(gemm):
             h = torch.nn.functional.rms_norm(xh, (Kh,), gw, 1e-6)
-            mq.bf16_gemm(h, Lg["w"], mq.MQ_OUT_BF16, yg)
+            gemm(h, Lg["w"], yg)
             pm = torch.nn.functional.silu(yg[:, :Kd]) * yg[:, Kd:]
-            mq.bf16_gemm(pm, Ld["w"], mq.MQ_OUT_BF16, yo)
-        t_m4, t_m16 = timed(mlp_nvfp4, 10), timed(mlp_bf16, 10)
+            gemm(pm, Ld["w"], yo)
+        t_m4 = gpu_ms(mlp_nvfp4, 10, 3)
+        t_m16 = gpu_ms(lambda: mlp_bf16(lambda a, w, o: mq.bf16_gemm(a, w, mq.MQ_OUT_BF16, o)), 10, 3)
+        t_mv = gpu_ms(lambda: mlp_bf16(lambda a, w, o: torch.matmul(a, w.t(), out=o)), 10, 3)
         mlp_flop = wl.layer_flops(M, Lg["layer"]) + wl.layer_flops(M, Ld["layer"])
         fused["mlp_block_chain"] = {"nvfp4_ms": round(t_m4, 4), "bf16_ms": round(t_m16, 4),
+                                    "vendor_library_bf16_ms": round(t_mv, 4),
                                     "nvfp4_tflops": round(mlp_flop / (t_m4 * 1e-3) * 1e-12, 1),
-                                    "x_vs_bf16": round(t_m16 / t_m4, 3)}
+                                    "x_vs_bf16": round(t_m16 / t_m4, 3),
+                                    "x_vs_vendor_library_bf16": round(t_mv / t_m4, 3)}
         del gu, xh, cd, sd, ch, sh, yg, yo
         torch.cuda.empty_cache()
 
     # ---- second workload: the paper's sweep axis (Section 4.4, Fig. 3: prefill speed-up over BF16
     # against context length / batch), as tokens M per prefill batch on the same layer set.
-    # Activations are generated on the device (N(0,1), 0.1 % of the channels scaled by 20: the
-    # recipe of the headline workload without its host generator); weights are the headline's. ----
+    # Activations follow the headline recipe, generated on the device; weights are the headline's.
+    # Up to 2048 tokens the launches are replayed from a HIP graph (a launch lasts 10 .. 100 us there). ----
     sweep = None
     if args.config == 2 and not args.no_sweep:
         sweep = {}
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(1234)
         for ms in (64, 128, 256, 512, 1024, 2048, 4096, 16384, 32768, 65536, 131072):
-            t_q4 = t_b16 = t_ven = 0.0
-            small = ms <= 1024
-            for L in layers:
-                K, N = L["layer"].K, L["layer"].N
-                x = torch.randn((ms, K), dtype=torch.bfloat16, device="cuda", generator=gen)
-                cols = torch.randperm(K, device="cuda", generator=gen)[:max(1, round(0.001 * K))]
-                x[:, cols] *= 20.0
-                ax = mq.nvfp4_global_scale(x)
-                xc = torch.empty((ms, K // 2), dtype=torch.uint8, device="cuda")
-                xs = torch.empty((ms, K // 16), dtype=torch.uint8, device="cuda")
-                y = torch.empty((ms, N), dtype=torch.bfloat16, device="cuda")
-
-                def one():
-                    mq.nvfp4_quantize(x, ax, xc, xs, LAYOUT)
-                    mq.nvfp4_gemm_ws(xc, xs, ax, L["wc"], L["ws"], L["aw"], GEMM_WS, mq.MQ_OUT_BF16, y, LAYOUT)
-
-                def ven():
-                    torch.matmul(x, L["w"].t(), out=y)
-                for fn, reps in ((one, 20 if small else 3),
-                                 (lambda: mq.bf16_gemm(x, L["w"], mq.MQ_OUT_BF16, y), 20 if small else 2),
-                                 (ven, 20 if small else 2)):
-                    fn()
-                    fn()
-                    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    s0.record()
-                    for _ in range(reps):
-                        fn()
-                    s1.record()
-                    torch.cuda.synchronize()
-                    if fn is one:
-                        t_q4 += s0.elapsed_time(s1) / reps
-                    elif fn is ven:
-                        t_ven += s0.elapsed_time(s1) / reps
-                    else:
-                        t_b16 += s0.elapsed_time(s1) / reps
-                del x, xc, xs, y
-            fl = sum(wl.layer_flops(ms, L["layer"]) for L in layers)
-            sweep[f"M={ms}"] = {"nvfp4_quant_plus_gemm_tflops": round(fl / (t_q4 * 1e-3) * 1e-12, 1),
-                                "bf16_gemm_tflops": round(fl / (t_b16 * 1e-3) * 1e-12, 1),
-                                "vendor_library_bf16_gemm_tflops": round(fl / (t_ven * 1e-3) * 1e-12, 1),
-                                "nvfp4_us": round(t_q4 * 1e3, 1),
-                                "x_vs_bf16_gemm": round(t_b16 / t_q4, 3),
-                                "x_vs_vendor_library_bf16_gemm": round(t_ven / t_q4, 3)}
+            small = ms <= 2048
+            specs = [(L["layer"].name, L["layer"].K, L["layer"].N, device_activation(cfg, L["layer"], ms), L["w"])
+                     for L in layers]
+            rec = measure_layer_set(ms, specs, 20 if small else 3, small)
+            rec["timing"] = "hip graph replay" if small else "eager launches"
+            sweep[f"M={ms}"] = rec
+            del specs
             torch.cuda.empty_cache()
 
     # ---- what the matrix pipe sustains on this machine for random FP16 operands (measured roof) ----
     for _ in range(3):
         mq.mfma_probe(20000)
     torch.cuda.synchronize()
-    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0, p1 = event(), event()
     p0.record()
     probe_flop = sum(mq.mfma_probe(20000) for _ in range(10))
     p1.record()
     torch.cuda.synchronize()
     mfma_sustained = probe_flop / (p0.elapsed_time(p1) * 1e-3) * 1e-12
 
+    facts = profile_facts(PROFILE_SUMMARY) if args.config == 2 else {}
+    traffic = float(facts["traffic_bytes_per_launch"]) if "traffic_bytes_per_launch" in facts else None
     result = {
         "metric": "nvfp4_prefill_gemm_tflops_quant_plus_gemm_m8192",
         "value": round(tflops, 2),
@@ -346,6 +416,9 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(statistics.median(step_ms), 4),
+        "ms_per_step_min": round(min(step_ms), 4),
+        "value_at_median_step": round(flop_step / (statistics.median(step_ms) * 1e-3) * 1e-12, 2),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -354,15 +427,19 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: prefill linear layers ({', '.join(L['layer'].name for L in layers)}) "
                                f"at M={M} tokens, NVFP4 W4A4, quantize+GEMM per layer", "M": M,
                    "layers": [[L["layer"].name, L["layer"].K, L["layer"].N] for L in layers]},
+        # exact NVFP4 (a 6-significant-bit operand, E4M3 scale per 16) cannot run on CDNA4's scaled
+        # FP4/FP8 MFMA: the roof of this path is the dense 16-bit MFMA rate, a quarter of the FP4 peak
         "pct_of_fp4_mfma_peak": round(100.0 * tflops / PEAK_MFMA_FP4, 2),
         "pct_of_16bit_mfma_peak": round(100.0 * tflops / PEAK_MFMA_16BIT, 2),
         "x_vs_bf16_gemm": round(bf16_ms_step / ms_per_step, 3),
+        "x_vs_vendor_library_bf16_gemm": None if lib_ms_step is None else round(lib_ms_step / ms_per_step, 3),
         "bf16_gemm_tflops": round(bf16_tflops, 2),
         "vendor_library_bf16_gemm_tflops": None if lib_tflops is None else round(lib_tflops, 2),
         "gemm_only_tflops": round(gemm_tflops, 2),
         "dynamic_alpha_pipeline_tflops": round(flop_step / (dyn_ms_step * 1e-3) * 1e-12, 2),
         "global_scale_gbs": round(amax_gbs, 1),
         "decode_bf16_gemm_weight_gbs": decode,
+        "other_configs": other_configs,
         "tokens_per_batch_sweep": sweep,
         "fused_producer_quantizers": fused,
         "quantizer_gbs": round(quant_gbs, 1),
@@ -370,7 +447,7 @@ def main() -> int:
         "per_layer_ms": {L["layer"].name: {"quantize": round(q_ms[i], 4), "gemm": round(g_ms[i], 4)}
                          for i, L in enumerate(layers)},
         "roofline": {
-            "kernel": "nvfp4 gemm (gemm_fp4_direct: 256x256 tile, 4 waves of 128x128, persistent)",
+            "kernel": facts.get("kernel", "nvfp4 gemm"),
             "bound": "mfma",
             "achieved": round(gemm_tflops, 2),
             "peak": PEAK_MFMA_16BIT,
@@ -383,10 +460,10 @@ def main() -> int:
             "frac_of_mfma_only_sustained": round(gemm_tflops / mfma_sustained, 4),
             "avg_launch_ms": round(gemm_ms_step / nl, 4),
             "flop_per_launch": flop_step / nl,
-            # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated on a plain
-            # 1 GiB copy) + WRITE_SIZE (x1.0), averaged over the four launches of a step
-            # (profiles/nvfp4_gemm_bf16_gemm_quantizer_llama8b_m8192.md)
-            "traffic": 0.540 * 2 ** 30 if args.config == 2 else None,
+            # HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
+            # scaled by what the counter reads for a plain copy: read from the tracked summary
+            "traffic": traffic,
+            "traffic_source": os.path.relpath(PROFILE_SUMMARY, ROOT) if traffic is not None else None,
         },
     }
 
@@ -402,6 +479,7 @@ def main() -> int:
         wc, ws = oracle.quantize(w_bits, aw)
         c0 = time.perf_counter()
         xc, xs = oracle.quantize(xb, ax)
+        cq = time.perf_counter()
         a = oracle.dequantize(xc, xs, ax)
         b = oracle.dequantize(wc, ws, aw)
         y = oracle.gemm_f64(a, b)
@@ -414,6 +492,7 @@ def main() -> int:
             "cores": oracle.num_threads(),
             "kind": "oracle",
             "seconds": round(c1 - c0, 2),
+            "quantizer_elements_per_s": round(rows * L["layer"].K / (cq - c0), 1),
             "sample": f"first {rows} of {M} rows of the {L['layer'].name} layer "
                       f"(K={L['layer'].K}, N={L['layer'].N}): quantize + dequantize + FP64 GEMM + BF16 rounding",
         }

@@ -25,7 +25,8 @@ def _check_producer(p_gpu_bits, ref_f64, min_equal):
     d = np.abs(bf16_ordinal(p_gpu_bits).astype(np.int64) - bf16_ordinal(ref_bits).astype(np.int64))
     assert d.max() <= 1, f"producer off by {d.max()} BF16 ulps"
     equal = float((d == 0).mean())
-    assert equal >= min_equal, equal
+    # a fraction only means something on enough elements: small tensors may miss by one element
+    assert equal >= min_equal or int((d != 0).sum()) <= 1, equal
     return equal
 
 
@@ -96,7 +97,7 @@ def test_rmsnorm_quantize(rows, K, eps):
     _, _, y = run(mq.MQ_LAYOUT_LINEAR, True)
     torch.cuda.synchronize()
     y_bits = host_bits(y)
-    equal = _check_producer(y_bits, ref, 0.995)
+    equal = _check_producer(y_bits, ref, 0.9999)
     _check_quantized(run, y_bits, alpha)
     print(f"\n[rmsnorm rows={rows} K={K}] producer equal to RNE(binary64) on {equal:.6f} of the elements")
 
