@@ -480,20 +480,27 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
     }
     uint4 rc[NSETS][NT];     // this lane's 32 codes of each operand tile, NSETS K steps
     uint32_t rs[NSETS][NT];  // the rows' four E4M3 scale bytes
-    auto load_step = [&](int kt, auto setc) {
+    // K steps are loaded in ascending order, so the four K-step bases advance by their strides
+    // (scalar additions) instead of being recomputed by 64-bit multiplications; a step past the
+    // end of K re-reads the last one (its products are multiplied by zero scales).
+    int next_t = k0 < KT ? k0 : KT - 1;
+    const char *pa_c = ta_c + (int64_t)next_t * g.a_c_step, *pb_c = tb_c + (int64_t)next_t * g.b_c_step;
+    const char *pa_s = ta_s + (int64_t)next_t * g.a_s_step, *pb_s = tb_s + (int64_t)next_t * g.b_s_step;
+    auto load_step = [&](auto setc) {
         constexpr int R = decltype(setc)::value;
-        kt = kt < KT ? kt : KT - 1;
-        auto rsrc = [](const char *base, int64_t off) {
-            return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base) + off, 0, -1, 0x00020000);
+        auto rsrc = [](const char *base) {
+            return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, -1, 0x00020000);
         };
-        const __amdgpu_buffer_rsrc_t rac = rsrc(ta_c, (int64_t)kt * g.a_c_step), rbc = rsrc(tb_c, (int64_t)kt * g.b_c_step);
-        const __amdgpu_buffer_rsrc_t ras = rsrc(ta_s, (int64_t)kt * g.a_s_step), rbs = rsrc(tb_s, (int64_t)kt * g.b_s_step);
+        const __amdgpu_buffer_rsrc_t rac = rsrc(pa_c), rbc = rsrc(pb_c), ras = rsrc(pa_s), rbs = rsrc(pb_s);
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
             const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < TM ? rac : rbc, (int)vc[q], 0, 0);
             rc[R][q] = make_uint4(c[0], c[1], c[2], c[3]);
             rs[R][q] = __builtin_amdgcn_raw_buffer_load_b32(q < TM ? ras : rbs, (int)vs[q], 0, 0);
         }
+        const int64_t adv = next_t + 1 < KT ? -1 : 0;  // all ones while K steps remain (no branch in the loop)
+        next_t -= (int)adv;
+        pa_c += g.a_c_step & adv, pb_c += g.b_c_step & adv, pa_s += g.a_s_step & adv, pb_s += g.b_s_step & adv;
     };
     // scales, expansion and MFMAs exactly as in gemm_fp4_direct (K index of a lane: 32h + 8p + j)
     uint32_t sg[NT];
@@ -557,7 +564,7 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
         sched_phase<NM, 0, VPER, 0, 0>();
         prep_scales(Next{}, kt + 1 < k1);
         expand_phase(Next{}, 0, fr[0]);
-        load_step(kt + NSETS, setc);
+        load_step(setc);  // K step kt + NSETS
         mfmas(fr[1]);
         sched_phase<NM, 0, VPER + 2, 0, (2 * NT + NM - 1) / NM>();
     };
@@ -568,7 +575,13 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
         if constexpr (NSETS > 3) fn(std::integral_constant<int, 3>{});
     };
     static_assert(NSETS >= 1 && NSETS <= 4, "one to four K steps in flight");
-    for_sets([&](auto u) { load_step(k0 + decltype(u)::value, u); });
+    // The first NSETS K steps, issued set by set.  (Left to the scheduler, the B loads of all sets
+    // went last, and the counter the compiler waits on in the loop then demanded that nearly
+    // everything in flight had landed before each K step: a prefetch distance of one step, not three.)
+    for_sets([&](auto u) {
+        load_step(u);
+        __builtin_amdgcn_sched_barrier(0);
+    });
     const float scale = (*g.a_alpha) * (*g.b_alpha);
     prep_scales(std::integral_constant<int, 0>{}, k0 < k1);
     expand_phase(std::integral_constant<int, 0>{}, 0, fr[0]);
