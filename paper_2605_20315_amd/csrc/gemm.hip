@@ -445,6 +445,53 @@ struct SmallCfg {
     static constexpr int TM = TM_, TN = TN_, WN = 32 * TN_;
 };
 
+// End of the small-tile kernels: the S waves of a workgroup hold partial sums of one
+// (32 TM) x (32 TN) tile over their parts of K.  S == 1: plain epilogue.  Otherwise the partial
+// tiles are added through LDS, four 32x32 tiles (16 KB per wave) per pass.  A pass holds 16 chunks
+// of four accumulator registers per wave; wave w adds the S copies of chunks w, w + S, ... in
+// wave order (bit-identical from run to run), scales, rounds and stores them: chunk c of a tile =
+// rows 8c + 4 (lane / 32) .. + 3, column lane % 32.
+template <int TM, int TN, bool OUT_BF16>
+__device__ __forceinline__ void small_tile_finish(const GemmArgs &g, f32x16 (&acc)[TM][TN], float scale, int64_t m0,
+                                                  int64_t n0, int S, int wave, int lane)
+{
+    constexpr int NM = TM * TN;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    if (S == 1) {
+        epilogue<SmallCfg<TM, TN>, OUT_BF16>(g, acc, scale, m0, n0, 0, 0, frow, fhalf);
+        return;
+    }
+    extern __shared__ uint4 lds[];
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4 *const X = reinterpret_cast<f32x4 *>(lds);
+    using T = std::conditional_t<OUT_BF16, __bf16, float>;
+    constexpr int PASS = NM < 4 ? NM : 4;  // tiles per pass
+#pragma unroll
+    for (int p0 = 0; p0 < NM; p0 += PASS) {
+        if (p0 > 0) __syncthreads();  // the previous pass has been read
+#pragma unroll
+        for (int u = 0; u < PASS; ++u) {
+            const f32x16 &tl = acc[(p0 + u) / TN][(p0 + u) % TN];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                X[((wave * PASS + u) * 4 + c) * 64 + lane] = f32x4{tl[4 * c], tl[4 * c + 1], tl[4 * c + 2], tl[4 * c + 3]};
+        }
+        __syncthreads();
+        for (int ch = wave; ch < PASS * 4; ch += S) {
+            f32x4 sum = X[ch * 64 + lane];
+            for (int w = 1; w < S; ++w) sum += X[(w * PASS * 4 + ch) * 64 + lane];
+            const int tile = p0 + (ch >> 2), c = ch & 3;
+            const int64_t n = n0 + (tile % TN) * 32 + frow;
+            const int64_t mrow = m0 + (tile / TN) * 32 + 8 * c + 4 * fhalf;
+            if (n < g.N) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (mrow + e < g.M) static_cast<T *>(g.y)[(mrow + e) * g.ldy + n] = (T)(sum[e] * scale);
+            }
+        }
+    }
+}
+
 template <int TM, int TN, int MAXS, int NSETS, bool OUT_BF16>
 __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tiles_m, int tiles_n)
 {
@@ -588,42 +635,7 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
     // whole groups of NSETS K steps; a step past the end multiplies by zero scales
     for (int kt = k0; kt < k1; kt += NSETS) for_sets([&](auto u) { kstep(kt + decltype(u)::value, u); });
 
-    if (S == 1) {
-        epilogue<SmallCfg<TM, TN>, OUT_BF16>(g, acc, scale, m0, n0, 0, 0, frow, fhalf);
-        return;
-    }
-    // Sum over the S waves through LDS, four 32x32 tiles (16 KB per wave) per pass.  A pass holds 16
-    // chunks of four accumulator registers per wave; wave w adds the S copies of chunks w, w + S,
-    // ... in wave order and stores them: chunk c of a tile = rows 8c + 4 (lane / 32) .. + 3.
-    extern __shared__ uint4 lds[];
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
-    f32x4 *const X = reinterpret_cast<f32x4 *>(lds);
-    using T = std::conditional_t<OUT_BF16, __bf16, float>;
-    constexpr int PASS = NM < 4 ? NM : 4;  // tiles per pass
-#pragma unroll
-    for (int p0 = 0; p0 < NM; p0 += PASS) {
-        if (p0 > 0) __syncthreads();  // the previous pass has been read
-#pragma unroll
-        for (int u = 0; u < PASS; ++u) {
-            const f32x16 &tl = acc[(p0 + u) / TN][(p0 + u) % TN];
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                X[((wave * PASS + u) * 4 + c) * 64 + lane] = f32x4{tl[4 * c], tl[4 * c + 1], tl[4 * c + 2], tl[4 * c + 3]};
-        }
-        __syncthreads();
-        for (int ch = wave; ch < PASS * 4; ch += S) {
-            f32x4 sum = X[ch * 64 + lane];
-            for (int w = 1; w < S; ++w) sum += X[(w * PASS * 4 + ch) * 64 + lane];
-            const int tile = p0 + (ch >> 2), c = ch & 3;
-            const int64_t n = n0 + (tile % TN) * 32 + frow;
-            const int64_t mrow = m0 + (tile / TN) * 32 + 8 * c + 4 * fhalf;
-            if (n < g.N) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (mrow + e < g.M) static_cast<T *>(g.y)[(mrow + e) * g.ldy + n] = (T)(sum[e] * scale);
-            }
-        }
-    }
+    small_tile_finish<TM, TN, OUT_BF16>(g, acc, scale, m0, n0, S, wave, lane);
 }
 
 // Second pass of the slab-split product: y[m][n] = round(scale * (ws[0][m][n] + ws[1][m][n] + ...)),
