@@ -173,19 +173,20 @@ int nvfp4_gemm(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_a
                void *stream);
 
 /*
- * The same product (Section 3.3) with a caller-owned workspace.  Prefill chunks of a few
- * hundred tokens have fewer 128x128 output tiles than the GPU has compute units, and the time
- * is then the time to stream the weights once; with a workspace the K dimension is cut into
- * slabs across workgroups, each writes FP32 partial sums to the workspace, and a second kernel
- * adds the slabs in ascending order, applies alpha_a * alpha_b and rounds.  Same arguments,
- * requirements, tolerance and run-to-run bit-identity as nvfp4_gemm; the summation order (and
- * so the last bits) may differ from nvfp4_gemm's where slabs are used.
+ * The same product (Section 3.3) with a caller-owned workspace.  A prefill chunk of a few
+ * hundred tokens against a layer with a long K and a narrow N has fewer output tiles than the GPU
+ * has compute units; with a workspace the K dimension is then cut into slabs across workgroups,
+ * each writes FP32 partial sums to the workspace, and a second kernel adds the slabs in ascending
+ * order, applies alpha_a * alpha_b and rounds.  Same arguments, requirements, tolerance and
+ * run-to-run bit-identity as nvfp4_gemm; the summation order (and so the last bits) may differ
+ * from nvfp4_gemm's where slabs are used.
  * workspace: device memory, 16-byte aligned, workspace_bytes >= 0 bytes, or NULL with 0; its
  * contents are undefined afterwards and it must not be used by other work on another stream
  * until this call's kernels have finished.  mq_gemm_workspace_bytes(M, N, K) (host function, no
- * GPU access) returns the size that lets the library choose freely (never more than 16 MiB; 0
- * where slabs are never used: N % 4 != 0, K % 64 != 0, K < 1024, or at least 64 output tiles
- * of 128x128); a smaller workspace is legal and only limits the number of slabs.
+ * GPU access) returns the size that lets the library choose freely: slabs * M * N * 4 bytes,
+ * never more than 4 MiB, and 0 where slabs are never used (N % 4 != 0, K % 64 != 0, more than 128
+ * output tiles of 64x64, or a K too short for the second pass to pay: below about 8192).  A
+ * smaller workspace is legal and only limits the number of slabs.
  */
 int64_t mq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
@@ -205,7 +206,7 @@ int nvfp4_gemm_ws(const uint8_t *a_codes, const uint8_t *a_scales, const float *
  * slab is written before it is read): calls that overlap in time on one GPU, from different
  * streams or threads, race on it; calls on one stream are ordered and safe.
  */
-#define MQ_NOALLOC_SCRATCH_BYTES (16u << 20)
+#define MQ_NOALLOC_SCRATCH_BYTES (4u << 20)
 int nvfp4_gemm_noalloc(const uint8_t *a_codes, const uint8_t *a_scales, const float *a_alpha_dev,
                        const uint8_t *b_codes, const uint8_t *b_scales, const float *b_alpha_dev,
                        int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, int layout,

@@ -162,15 +162,14 @@ static int check_out(const void *y, int64_t N, int64_t ldy, int out)
 }
 
 // gfx950 parts have at most 256 compute units; the launcher uses what the device reports and
-// at most one 128x128 FP32 tile per compute unit.
+// at most one 64x64 FP32 tile of partial sums per compute unit.
 static constexpr int kMaxComputeUnits = 256;
 
 int64_t mq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
 {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    if (gemm_fp4_small_waves(M, N, K, INT64_MAX, kMaxComputeUnits) > 0) return 0;  // one launch, no partial sums
-    const int ks = gemm_fp4_ksplit(M, N, K, INT64_MAX, kMaxComputeUnits);
-    return ks >= 2 ? (int64_t)ks * M * N * 4 : 0;
+    const SmallPlan plan = gemm_fp4_small_plan(M, N, K, INT64_MAX, kMaxComputeUnits);
+    return plan.waves > 0 && plan.slabs >= 2 ? (int64_t)plan.slabs * M * N * 4 : 0;
 }
 
 int mq_init(void) { return ensure_device(nullptr); }

@@ -18,8 +18,10 @@
 //                       each wave loads its own operand rows in MFMA order and expands them in
 //                       registers (described at the kernel).  A 256x256 tile, a 256x128 tile
 //                       with K split over wave pairs, or a 128x128 tile with K split over all
-//                       four waves and, for a few hundred tokens and with a workspace, also
-//                       over workgroups (splitk_reduce_kernel then adds the slabs).
+//                       four waves.
+//   gemm_fp4_small      NVFP4 problems of up to 2 x CUs tiles of 64x64 (a few hundred tokens): one
+//                       workgroup per tile, K split over its waves; for a long K with very few
+//                       tiles also over workgroups (splitk_reduce_kernel then adds the slabs).
 //   gemm_bf16_d2l       the BF16 baseline on large problems: 256x256 tile, four waves of 128x128,
 //                       tiles loaded from global memory straight into LDS.
 //   gemm_bf16_pipelined the BF16 baseline on smaller problems, same LDS pipeline, tiles staged
@@ -185,14 +187,9 @@ struct RawTile {
 // hands the half of its accumulators that its partner will store to the partner through LDS.
 // SPLIT = 4: the workgroup tile is one 128x128 wave tile, its four waves take a quarter of K
 // each, and two such exchanges leave every wave with 32 fully summed rows to store.
-// XSPLIT (with SPLIT = 4; problems with fewer 128x128 tiles than compute units, i.e. a few
-// hundred tokens): K is also cut into g.ksplit slabs across workgroups.  A work item is (slab,
-// tile); its workgroup writes the FP32 partial sums of the slab to g.ws[slab][M][N] (unscaled),
-// and splitk_reduce_kernel adds the slabs in ascending order, scales and rounds.
-template <bool OUT_BF16, int SPLIT, bool XSPLIT = false>
+template <bool OUT_BF16, int SPLIT>
 __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, int tiles_n)
 {
-    static_assert(!XSPLIT || SPLIT == 4, "slabs of K across workgroups: only with the four-way split inside");
     using C = PCfg<256, 256, 2, 2>;  // wave-level constants: 128x128 wave tile, 4x4 MFMA tiles
     static_assert(SPLIT == 1 || SPLIT == 2 || SPLIT == 4, "K is split over 1, 2 or 4 waves");
     constexpr int BM = SPLIT == 4 ? 128 : 256, BN = SPLIT == 1 ? 256 : 128;
@@ -210,26 +207,11 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = (int)(g.K / BK);
     // this wave's K steps [k0, k1); every part but the last is a whole number of NSETS groups
-    const int parts = SPLIT * (XSPLIT ? g.ksplit : 1);
+    const int parts = SPLIT;
     const int KH = SPLIT == 1 ? KT : ((KT + parts - 1) / parts + NSETS - 1) / NSETS * NSETS;
     int k0 = kpart * KH, k1 = (k0 + KH < KT) ? k0 + KH : KT;
-    const int tiles = tiles_m * tiles_n;
-    const int total_tiles = XSPLIT ? tiles * g.ksplit : tiles;  // work items
-    int slab = 0;
-    // work item -> tile and, with XSPLIT, K slab (items of one slab are contiguous, so that the
-    // workgroups of an XCD share a slab of A)
-    auto item_of = [&](int item, int &tm, int &tn) {
-        if constexpr (XSPLIT) {
-            const int t = logical_id(item, total_tiles);
-            slab = t / tiles;
-            tile_of_logical(t - slab * tiles, tiles_m, tiles_n, tm, tn);
-            k0 = (slab * SPLIT + kpart) * KH;
-            k0 = k0 < KT ? k0 : KT;  // a wave past the end sums nothing
-            k1 = (k0 + KH < KT) ? k0 + KH : KT;
-        } else {
-            tile_of(item, tiles_m, tiles_n, tm, tn);
-        }
-    };
+    const int total_tiles = tiles_m * tiles_n;
+    auto item_of = [&](int item, int &tm, int &tn) { tile_of(item, tiles_m, tiles_n, tm, tn); };
 
     // Buffer loads: per K step a uniform resource whose 64-bit base is the start of that K step
     // (scalar arithmetic only), plus the lane's row and half as a 32-bit vector offset.  Rows
@@ -367,7 +349,6 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         }
         tile += gridDim.x;
         const bool more = tile < total_tiles;
-        const int done_slab = slab;
         if (more) {
             item_of(tile, tm, tn);
             set_tile((int64_t)tm * BM, (int64_t)tn * BN);
@@ -414,14 +395,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
                 epilogue<C, OUT_BF16, 0, 2>(g, acc, scale, m0, n0, wm0 + kpart * 64, wn0, frow, fhalf);
             } else {
                 exchange(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{}, wave ^ 1);
-                if constexpr (XSPLIT) {
-                    GemmArgs part = g;  // the slab's [M, N] FP32 matrix of partial sums
-                    part.y = g.ws + (int64_t)done_slab * g.M * g.N;
-                    part.ldy = g.N;
-                    epilogue<C, false, 0, 1>(part, acc, 1.0f, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
-                } else {
-                    epilogue<C, OUT_BF16, 0, 1>(g, acc, scale, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
-                }
+                epilogue<C, OUT_BF16, 0, 1>(g, acc, scale, m0, n0, wm0 + wave * 32, wn0, frow, fhalf);
             }
         }
         if (!more) break;
@@ -437,7 +411,10 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
 // order, expanded in registers, no LDS and no barrier in the loop) with NSETS K steps of codes in
 // flight per wave.  The S partial tiles are then added through LDS in a fixed order (wave 0, 1,
 // ...: bit-identical from run to run), each wave summing, scaling, rounding and storing 1/S of the
-// tile.  No workspace and no second kernel: one launch per layer.  Smaller wave tiles raise the
+// tile.  No workspace and no second kernel: one launch per layer.  Only a long K with very few
+// tiles is also cut into g.ksplit slabs across workgroups when the caller passes a workspace: a
+// work item is then (slab, tile), its workgroup writes unscaled FP32 partial sums to
+// g.ws[slab][M][N], and splitk_reduce_kernel adds the slabs in ascending order.  Smaller wave tiles raise the
 // conversion work per MFMA (TM + TN operand tiles expanded for TM x TN MFMAs: 8 VALU instructions
 // per MFMA for 64x64, 6 for 128x64) but multiply the number of waves that pull on memory.
 template <int TM_, int TN_>
@@ -502,13 +479,19 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
     const int S = (int)(blockDim.x >> 6);  // waves that share this tile's K range
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = (int)(g.K / BK);
-    const int KH = (KT + S - 1) / S;
-    const int k0 = wave * KH < KT ? wave * KH : KT;
-    const int k1 = k0 + KH < KT ? k0 + KH : KT;
-    // tiles that share a column panel of B are neighbours in the tile order and run on one XCD
-    const int t = logical_id(blockIdx.x, tiles_m * tiles_n);
+    // work item = (K slab, tile), slab-major; tiles that share a column panel of B are neighbours
+    // in that order and run on one XCD.  g.ksplit == 1: the tile's whole K.
+    const int tiles = tiles_m * tiles_n;
+    const int item = logical_id(blockIdx.x, tiles * g.ksplit);
+    const int slab = item / tiles, t = item - slab * tiles;
     const int tm = t % tiles_m, tn = t / tiles_m;
     const int64_t m0 = (int64_t)tm * (32 * TM), n0 = (int64_t)tn * (32 * TN);  // m0 < M, n0 < N
+    // K steps of the slab, then of this wave within it
+    const int SL = (KT + g.ksplit - 1) / g.ksplit;
+    const int s0 = slab * SL < KT ? slab * SL : KT, s1 = s0 + SL < KT ? s0 + SL : KT;
+    const int KH = (s1 - s0 + S - 1) / S;
+    const int k0 = s0 + wave * KH < s1 ? s0 + wave * KH : s1;
+    const int k1 = k0 + KH < s1 ? k0 + KH : s1;
 
     // operand q: A row tile q (q < TM), else B row tile q - TM.  Lane offsets relative to the tile.
     const char *const ta_c = static_cast<const char *>(g.a) + m0 * g.a_c_row;
@@ -635,7 +618,14 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
     // whole groups of NSETS K steps; a step past the end multiplies by zero scales
     for (int kt = k0; kt < k1; kt += NSETS) for_sets([&](auto u) { kstep(kt + decltype(u)::value, u); });
 
-    small_tile_finish<TM, TN, OUT_BF16>(g, acc, scale, m0, n0, S, wave, lane);
+    if (g.ksplit > 1) {
+        GemmArgs part = g;  // the slab's [M, N] FP32 matrix of partial sums; splitk_reduce_kernel scales and rounds
+        part.y = g.ws + (int64_t)slab * g.M * g.N;
+        part.ldy = g.N;
+        small_tile_finish<TM, TN, false>(part, acc, 1.0f, m0, n0, S, wave, lane);
+    } else {
+        small_tile_finish<TM, TN, OUT_BF16>(g, acc, scale, m0, n0, S, wave, lane);
+    }
 }
 
 // Second pass of the slab-split product: y[m][n] = round(scale * (ws[0][m][n] + ws[1][m][n] + ...)),
@@ -1180,14 +1170,21 @@ int launch_persistent(Kern kern, int bm, int bn, size_t lds_bytes, const GemmArg
 
 // One workgroup of S waves per (32 TM) x (32 TN) tile.
 template <int TM, int TN, int MAXS, int NSETS, bool OUT_BF16>
-int launch_small(const GemmArgs &g, hipStream_t s, int S)
+int launch_small(const GemmArgs &g0, hipStream_t s, SmallPlan plan)
 {
+    const int S = plan.waves;
+    GemmArgs g = g0;
+    g.ksplit = plan.slabs;
     const int64_t tiles_m = (g.M + 32 * TM - 1) / (32 * TM), tiles_n = (g.N + 32 * TN - 1) / (32 * TN);
-    if (tiles_m * tiles_n > 0x7FFFFFFF || S < 1 || S > MAXS) return MQ_ERR_SHAPE;
+    if (tiles_m * tiles_n * g.ksplit > 0x7FFFFFFF || S < 1 || S > MAXS || g.ksplit < 1) return MQ_ERR_SHAPE;
     constexpr int PASS = TM * TN < 4 ? TM * TN : 4;
     const size_t lds = S > 1 ? (size_t)S * PASS * 4096 : 0;
     gemm_fp4_small<TM, TN, MAXS, NSETS, OUT_BF16>
-        <<<dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * S), lds, s>>>(g, (int)tiles_m, (int)tiles_n);
+        <<<dim3((unsigned)(tiles_m * tiles_n * g.ksplit)), dim3(64 * S), lds, s>>>(g, (int)tiles_m, (int)tiles_n);
+    int rc = note_launch(hipGetLastError());
+    if (rc != MQ_OK || g.ksplit == 1) return rc;
+    const int64_t quads = g.M * (g.N / 4);
+    splitk_reduce_kernel<OUT_BF16><<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(g);
     return note_launch(hipGetLastError());
 }
 
@@ -1245,36 +1242,19 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         // being charged 55 / 34 percent of a whole one (measured on M = 512 .. 8192).
         int cus = 0;
         if (int rc = compute_units(cus)) return rc;
-        // A few hundred tokens: 64x64 tiles with K split over the waves of a workgroup, one launch
-        // (or, for a long K with very few tiles and a workspace, slabs of K across workgroups).
-        const int sw = gemm_fp4_small_waves(g.M, g.N, g.K, g.ws ? g.ws_bytes : 0, cus);
-        if (sw > 0) return launch_small<2, 2, 8, 4, OUT_BF16>(g, s, sw);
+        // A few hundred tokens (at most 2 x CUs tiles of 64x64): the small-tile kernel, one launch
+        // (plus, for a long K with very few tiles and a workspace, slabs of K across workgroups).
+        const SmallPlan plan = gemm_fp4_small_plan(g.M, g.N, g.K, g.ws ? g.ws_bytes : 0, cus);
+        if (plan.waves > 0) return launch_small<2, 2, 8, 4, OUT_BF16>(g, s, plan);
+        // From here on the 128x128 wave tiles fill at least half of the chip.
         const int64_t small_tiles = ((g.M + 127) / 128) * ((g.N + 127) / 128);
         const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus,
                       r4 = (small_tiles + cus - 1) / cus;
-        if (2 * small_tiles >= cus) {
-            const int64_t c1 = 100 * r1, c2 = 55 * r2, c4 = 34 * r4;
-            if (2 * mid_tiles < cus || (c4 < c1 && c4 < c2))
-                return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus);
-            if (c2 < c1)
-                return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus);
-            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus);
-        }
-        // Fewer 128x128 tiles than half the compute units (a few hundred tokens): the time is the
-        // weights' way from HBM, and only more workgroups pull harder.  With a workspace, K is cut
-        // into slabs across workgroups (one round of work items) and a second kernel adds the
-        // slabs; without one, the four-way split inside the workgroup is what there is.
-        const int ks = gemm_fp4_ksplit(g.M, g.N, g.K, g.ws ? g.ws_bytes : 0, cus);
-        if (ks >= 2) {
-            GemmArgs gs = g;
-            gs.ksplit = ks;
-            if (int rc = launch_persistent(gemm_fp4_direct<OUT_BF16, 4, true>, 128, 128, 128 * 1024, gs, s, cus, ks))
-                return rc;
-            const int64_t quads = g.M * (g.N / 4);
-            splitk_reduce_kernel<OUT_BF16><<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(gs);
-            return note_launch(hipGetLastError());
-        }
-        return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus);
+        const int64_t c1 = 100 * r1, c2 = 55 * r2, c4 = 34 * r4;
+        if (2 * mid_tiles < cus || (c4 < c1 && c4 < c2))
+            return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus);
+        if (c2 < c1) return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus);
+        return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus);
     } else {
         // Same choice by rounds of workgroups as above: 256x256 tiles, or 256x128 tiles (half the
         // work per workgroup, somewhat less efficient) when they waste less of the last round;
@@ -1313,7 +1293,6 @@ int configure_gemm_kernels()
     };
     both(gemm_fp4_direct<true, 2>, gemm_fp4_direct<false, 2>, X);
     both(gemm_fp4_direct<true, 4>, gemm_fp4_direct<false, 4>, X);
-    both(gemm_fp4_direct<true, 4, true>, gemm_fp4_direct<false, 4, true>, X);
     both(gemm_fp4_small<2, 2, 8, 4, true>, gemm_fp4_small<2, 2, 8, 4, false>, X);
     both(gemm_bf16_d2l<D, true>, gemm_bf16_d2l<D, false>, D::LDS_BYTES);
     both(gemm_bf16_d2l<Mid, true>, gemm_bf16_d2l<Mid, false>, Mid::LDS_BYTES);
@@ -1321,44 +1300,32 @@ int configure_gemm_kernels()
     return note_launch(e);
 }
 
-// Waves per 64x64 tile if the small-tile kernel serves this problem, else 0.  Measured on the
-// Llama-3-8B layer set at 64 .. 1024 tokens (one GPU, times of one launch inside a HIP graph): up
-// to 2 x CUs tiles of 64x64 it beats the 128x128 wave tiles (M = 128, N = 4096, K = 4096: 10.9 us
-// against 19.2 with slabs and 27 without), beyond that the larger tiles' lower conversion work
-// per MFMA wins.  Eight waves per tile (two per SIMD) while every tile gets a compute unit of
-// its own, four beyond.  Exception: a long K with very few tiles and a workspace at hand, where
-// slabs of K across workgroups occupy more compute units (M = 64, N = 4096, K = 14336: 23.6 us
-// against 25.5).
-int gemm_fp4_small_waves(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
+// Does the small-tile kernel serve this problem, with how many waves per 64x64 tile and how
+// many K slabs across workgroups?  Measured on the Llama-3-8B layer set at 64 .. 1024 tokens (one
+// GPU, one launch inside a HIP graph): up to 2 x CUs tiles of 64x64 it beats the 128x128 wave tiles
+// (M = 128, N = 4096, K = 4096: 10.9 us against 19.2 with slabs of 128x128 tiles and 27 without),
+// beyond that the larger tiles' lower conversion work per MFMA wins.  Eight waves per tile (two
+// per SIMD) while every tile gets a compute unit of its own, four beyond.  A launch costs about
+// 6.5 us plus 0.5 us per K step of a wave; slabs add a second launch and the partial sums' way
+// through the workspace, about 4.5 us: they are used when at most half of the compute units
+// would otherwise hold a tile and the K steps they take off each wave are worth more than that.
+SmallPlan gemm_fp4_small_plan(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
 {
-    if (M <= 0 || N <= 0 || K % BK != 0) return 0;
+    SmallPlan plan{0, 1};
+    if (M <= 0 || N <= 0 || K <= 0 || K % BK != 0) return plan;
     const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64), kt = K / BK;
-    if (tiles > 2 * (int64_t)cus) return 0;
-    if (2 * tiles <= cus && kt >= 128 && gemm_fp4_ksplit(M, N, K, ws_bytes, cus) >= 2) return 0;
+    if (tiles > 2 * (int64_t)cus) return plan;
     int64_t waves = tiles <= cus ? 8 : 4;
     if (waves > kt / 2) waves = kt / 2 > 0 ? kt / 2 : 1;  // at least two K steps per wave
-    return (int)waves;
-}
-
-int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
-{
-    if (M <= 0 || N <= 0 || K % BK != 0 || N % 4 != 0 || ws_bytes <= 0) return 1;
-    const int64_t small_tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    if (2 * small_tiles >= cus) return 1;  // enough tiles: no slabs
-    const int64_t kt = K / BK;
-    int64_t ks_max = cus / small_tiles;    // one round of work items
-    if (ks_max > kt / 8) ks_max = kt / 8;  // at least two K steps for each of a workgroup's four waves
-    const int64_t fit = ws_bytes / (M * N * 4);
-    if (ks_max > fit) ks_max = fit;
-    // Cost in ns: a wave's K steps (1.1 us each, measured) plus, with slabs, the second launch and
-    // the partial sums' way to the workspace and back (4 TB/s).
-    int64_t best = 1, best_cost = INT64_MAX;
-    for (int64_t ks = 1; ks <= ks_max; ++ks) {
-        const int64_t kh = ((kt + 4 * ks - 1) / (4 * ks) + 1) / 2 * 2;
-        const int64_t cost = kh * 1100 + (ks > 1 ? 3000 + ks * M * N * 8 / 4000 : 0);
-        if (cost < best_cost) best = ks, best_cost = cost;
+    plan.waves = (int)waves;
+    if (ws_bytes > 0 && N % 4 == 0 && 2 * tiles <= cus) {
+        int64_t ks = cus / tiles;                                  // one round of work items
+        if (ks > kt / (waves * 4)) ks = kt / (waves * 4);          // at least four K steps per wave
+        if (ks > ws_bytes / (M * N * 4)) ks = ws_bytes / (M * N * 4);
+        // K-loop time saved, (kt / waves) * (1 - 1 / ks) * 0.5 us, against 4.5 us for the second pass
+        if (ks >= 2 && kt * (ks - 1) > 9 * waves * ks) plan.slabs = (int)ks;
     }
-    return (int)best;
+    return plan;
 }
 
 int launch_mfma_probe(float *out, int iters, int blocks, hipStream_t s)

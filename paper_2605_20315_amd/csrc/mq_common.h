@@ -54,16 +54,20 @@ struct GemmArgs {
     void *y;
     int64_t ldy;
     int out;                  // mq_out
-    // optional workspace for partial sums (NVFP4, problems of a few 128x128 tiles): ws_bytes of
-    // device memory, 16-byte aligned, or NULL / 0.  ksplit is filled in by the launcher.
+    // optional workspace for partial sums (NVFP4, a long K with very few output tiles): ws_bytes of
+    // device memory, 16-byte aligned, or NULL / 0.  ksplit (K slabs across workgroups, >= 1) is
+    // filled in by the launcher.
     float *ws;
     int64_t ws_bytes;
     int ksplit;
 };
-// K slabs the NVFP4 launcher would cut a problem into (1: none), given this much workspace
-int gemm_fp4_ksplit(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
-// waves per 64x64 tile if the small-tile NVFP4 kernel serves this problem (given this much workspace), else 0
-int gemm_fp4_small_waves(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
+// Plan of the small-tile NVFP4 kernel for a problem, given this much workspace: waves per 64x64
+// tile (0: another kernel serves the problem) and K slabs across workgroups (1: none).
+struct SmallPlan {
+    int waves;
+    int slabs;
+};
+SmallPlan gemm_fp4_small_plan(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
 // sets the dynamic-LDS limit of every tiled kernel on the current device (idempotent)
 int configure_gemm_kernels();
 int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);

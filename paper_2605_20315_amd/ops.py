@@ -150,7 +150,7 @@ def mq_init() -> None:
     _lib.check(_lib.load().mq_init(), "mq_init")
 
 
-NOALLOC_SCRATCH_BYTES = 16 << 20
+NOALLOC_SCRATCH_BYTES = 4 << 20
 
 
 def nvfp4_gemm_noalloc(a_codes, a_scales, a_alpha, b_codes, b_scales, b_alpha, out: int = MQ_OUT_BF16,

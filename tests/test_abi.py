@@ -85,14 +85,15 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
 
 
 def test_workspace_size_query(lib):
-    """Host-only: slabs of K across workgroups are offered only for a long K (at least 128 K steps)
-    with at most 128 output tiles of 64x64; the size is slabs * M * N * 4 bytes and never exceeds
-    one 128x128 FP32 tile per compute unit of the largest gfx950 part (256 x 64 KiB)."""
+    """Host-only: slabs of K across workgroups are offered only where they pay: at most 128 output
+    tiles of 64x64 and a K long enough that the K steps taken off each wave outweigh the second
+    pass; the size is slabs * M * N * 4 bytes and never exceeds one 64x64 FP32 tile per compute
+    unit of the largest gfx950 part (256 x 16 KiB = 4 MiB)."""
     q = lib.mq_gemm_workspace_bytes
-    assert q(8192, 4096, 4096) == 0          # 2048 tiles of 128x128
+    assert q(8192, 4096, 4096) == 0          # 8192 tiles
     assert q(128, 28672, 4096) == 0          # 896 tiles of 64x64
     assert q(128, 4096, 4096) == 0           # 64 K steps: the one-launch small-tile kernel
-    assert q(256, 4096, 14336) == 0          # 256 tiles of 64x64: small-tile kernel
+    assert q(256, 4096, 14336) == 0          # 256 tiles of 64x64: every compute unit has one
     assert q(128, 4098, 14336) == 0          # N % 4 != 0
     assert q(128, 4096, 14320) == 0          # K % 64 != 0
     assert q(0, 4096, 4096) == 0 and q(128, 0, 4096) == 0 and q(128, 4096, 0) == 0
@@ -100,9 +101,9 @@ def test_workspace_size_query(lib):
         b = q(M, N, K)
         assert b > 0 and b % (M * N * 4) == 0
         slabs = b // (M * N * 4)
-        tiles = -(-M // 128) * -(-N // 128)
-        assert 2 <= slabs <= min(256 // tiles, K // 512)
-        assert b <= 256 * 128 * 128 * 4
+        tiles = -(-M // 64) * -(-N // 64)
+        assert 2 <= slabs <= min(256 // tiles, K // 2048)      # at least four K steps for each of eight waves
+        assert b <= 256 * 64 * 64 * 4
 
 
 def test_binding_refuses_cpu_tensors():

@@ -32,19 +32,21 @@ def _reference(ac, asc, aa, bc, bsc, ba):
     return oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b)
 
 
-# (M, N, K).  Slabs of K across workgroups (with a workspace) need K >= 8192 and at most 128 tiles
-# of 64x64; with 256 compute units the launcher picks up to min(256 / tiles of 128x128, K / 512)
-# of them.  (100, 520, 8192): 5 tiles, 8 slabs; (128, 4096, 14336): 32 tiles, 7 slabs, 224 K steps
-# do not divide evenly; (300, 264, 8192): 9 tiles; (64, 1032, 12288): odd N tail; (17, 136, 8192):
-# 2 tiles, 16 slabs; (130, 2048, 8256): 129 K steps, slabs with idle waves.  The shapes with a
-# shorter K take the one-launch small-tile kernel with or without a workspace.
-SHAPES = [(100, 520, 8192), (128, 4096, 14336), (300, 264, 8192), (64, 1032, 12288), (17, 136, 8192),
-          (130, 2048, 8256), (1, 8, 8192), (100, 520, 4096), (300, 264, 1024), (64, 1032, 1536), (1, 8, 1024)]
+# (M, N, K, slabs expected with a full workspace).  Slabs of K across workgroups need at most 128
+# tiles of 64x64 and a K long enough to pay for the second pass; the launcher picks up to
+# min(256 / tiles, K / 2048) of them.  (100, 520, 8192): 18 tiles, 4 slabs; (128, 4096, 14336): 128
+# tiles, 2 slabs, 224 K steps; (300, 264, 8192): 25 tiles; (64, 1032, 12288): 6 slabs of 32 K steps,
+# odd N tail; (17, 136, 8192): 3 tiles; (130, 2048, 8256): 96 tiles, 129 K steps: too short for two
+# slabs to pay; (1, 8, 8192): one tile.  A shorter K takes the one-launch kernel with or without a
+# workspace.
+SHAPES = [(100, 520, 8192, True), (128, 4096, 14336, True), (300, 264, 8192, True), (64, 1032, 12288, True),
+          (17, 136, 8192, True), (130, 2048, 8256, False), (1, 8, 8192, True), (100, 520, 4096, False),
+          (300, 264, 1024, False), (64, 1032, 1536, False), (1, 8, 1024, False), (64, 264, 20544, True)]
 
 
-@pytest.mark.parametrize("M,N,K", SHAPES)
+@pytest.mark.parametrize("M,N,K,slabs", SHAPES)
 @pytest.mark.parametrize("layout", [mq.MQ_LAYOUT_KTILE, mq.MQ_LAYOUT_LINEAR])
-def test_small_m_with_and_without_workspace(M, N, K, layout):
+def test_small_m_with_and_without_workspace(M, N, K, slabs, layout):
     ops = _operands(M, N, K, 0)
     ref, na, nb = _reference(*ops)
     ac, asc, aa, bc, bsc, ba = ops
@@ -53,7 +55,7 @@ def test_small_m_with_and_without_workspace(M, N, K, layout):
     a_al, b_al = dev_scalar(aa), dev_scalar(ba)
     need = mq.mq_gemm_workspace_bytes(M, N, K)
     assert 0 <= need <= 16 << 20
-    assert (need > 0) == (K >= 8192)
+    assert (need > 0) == slabs
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     got = {}
     for out in (mq.MQ_OUT_BF16, mq.MQ_OUT_FP32):
