@@ -221,17 +221,6 @@ int nvfp4_gemm_noalloc(const uint8_t *a_codes, const uint8_t *a_scales, const fl
 int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw,
               int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream);
 
-/*
- * Diagnostic, not part of the method: enqueue a loop of `iters` x 8 independent FP16 MFMAs
- * (32x32x16) per wave on pseudo-random register operands, one wave per SIMD on 256 compute
- * units, with no memory traffic.  Timing it gives the matrix rate the chip sustains under its
- * power management for realistic operand toggling, the measured roof quoted beside the
- * published peak.  scratch_dev: at least one float of device memory (practically never
- * written).  *flop_out (host pointer, may be NULL) receives the flop count of the launch.
- * 1 <= iters <= 2^20.
- */
-int mq_mfma_probe(float *scratch_dev, int iters, void *stream, double *flop_out);
-
 /* Human-readable name of an mq_status value (static storage). */
 const char *mq_status_string(int status);
 

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/mixquant.h"
+#include "../../include/mixquant_diag.h"
 
 namespace mq {
 
