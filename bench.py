@@ -66,6 +66,8 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the tokens-per-batch sweep (second workload)")
     ap.add_argument("--no-fused", action="store_true", help="skip the producer-fused quantizers and the MLP chain")
     ap.add_argument("--no-configs", action="store_true", help="skip the other four workload configurations")
+    ap.add_argument("--sweep-m", type=str, default="64,128,256,512,1024,2048,4096,16384,32768,65536,131072",
+                    help="token counts of the sweep (comma-separated)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -89,8 +91,8 @@ def main() -> int:
     M = cfg.M
     LAYOUT = mq.MQ_LAYOUT_KTILE     # K-step-major NVFP4 bytes: the layout the GEMM streams
     # caller-owned workspace of the NVFP4 product (used only for a long K with very few output
-    # tiles, where K is cut into slabs across workgroups); the library's largest request is 16 MiB
-    GEMM_WS = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")
+    # tiles, where K is cut into slabs across workgroups); the library's largest request is 4 MiB
+    GEMM_WS = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -385,7 +387,7 @@ def main() -> int:
     sweep = None
     if args.config == 2 and not args.no_sweep:
         sweep = {}
-        for ms in (64, 128, 256, 512, 1024, 2048, 4096, 16384, 32768, 65536, 131072):
+        for ms in [int(v) for v in args.sweep_m.split(",") if v]:
             small = ms <= 2048
             specs = [(L["layer"].name, L["layer"].K, L["layer"].N, device_activation(cfg, L["layer"], ms), L["w"])
                      for L in layers]
