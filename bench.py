@@ -232,13 +232,22 @@ def main() -> int:
     lib_tflops = None if lib_ms_step is None else flop_step / (lib_ms_step * 1e-3) * 1e-12
 
     # ---- decode shapes of the high-precision path: a few tokens against the same weights (HBM-bound) ----
-    decode = {}
+    decode, decode_vendor = {}, {}
     w_bytes = sum(2.0 * L["layer"].N * L["layer"].K for L in layers)
-    for md in (1, 16, 32, 64):
+    dec_ws = torch.empty(16 << 20, dtype=torch.uint8, device="cuda")    # the largest the library asks for
+    for md in (1, 16, 32, 48, 64):
         def dec_step():
             for L in layers:
-                mq.bf16_gemm(L["x"][:md], L["w"], mq.MQ_OUT_BF16, L["y"][:md])
+                mq.bf16_gemm_ws(L["x"][:md], L["w"], dec_ws, mq.MQ_OUT_BF16, L["y"][:md])
         decode[f"M={md}"] = round(w_bytes / (gpu_ms(dec_step, 20, 3, graph=True) * 1e-3) * 1e-9, 1)
+        try:
+            def dec_lib():
+                for L in layers:
+                    torch.matmul(L["x"][:md], L["w"].t(), out=L["y"][:md])
+            decode_vendor[f"M={md}"] = round(w_bytes / (gpu_ms(dec_lib, 20, 3, graph=True) * 1e-3) * 1e-9, 1)
+        except Exception as exc:  # context only
+            print(f"bench.py: torch.matmul decode reference skipped: {exc}", file=sys.stderr)
+    del dec_ws
 
     # ---- one configuration's layer set on device-resident tensors: quantizer, GEMM, both, baselines ----
     def measure_layer_set(mm, specs, reps, graph):
@@ -441,6 +450,7 @@ def main() -> int:
         "dynamic_alpha_pipeline_tflops": round(flop_step / (dyn_ms_step * 1e-3) * 1e-12, 2),
         "global_scale_gbs": round(amax_gbs, 1),
         "decode_bf16_gemm_weight_gbs": decode,
+        "decode_vendor_library_bf16_gemm_weight_gbs": decode_vendor,
         "other_configs": other_configs,
         "tokens_per_batch_sweep": sweep,
         "fused_producer_quantizers": fused,

@@ -221,6 +221,23 @@ int nvfp4_gemm_noalloc(const uint8_t *a_codes, const uint8_t *a_scales, const fl
 int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw,
               int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out, void *stream);
 
+/*
+ * The same product with a caller-owned workspace, for decode batches (the precision that the
+ * decode phase keeps, Section 3.3): 33 to 64 tokens against a weight matrix with a narrow N leave
+ * most compute units without a row group of W, and the time is the weights' one trip from HBM;
+ * with a workspace K is cut into slabs across workgroups (FP32 partial sums, added in ascending
+ * order by a second kernel: bit-identical from run to run; the last bits may differ from
+ * bf16_gemm's).  Arguments and requirements as bf16_gemm; workspace as in nvfp4_gemm_ws.
+ * mq_bf16_gemm_workspace_bytes(M, N, K) (host function) returns the size that lets the library
+ * choose freely: slabs * M * N * 4 bytes (at most 16 MiB), 0 where slabs are never used
+ * (M <= 32, M > 64, N % 4 != 0, K % 128 != 0, K < 8192, N > 16256, or so few rows of W that even
+ * with slabs half of the compute units would stay empty).
+ */
+int64_t mq_bf16_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int bf16_gemm_ws(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw,
+                 int64_t M, int64_t N, int64_t K, void *y, int64_t ldy, int out,
+                 void *workspace, int64_t workspace_bytes, void *stream);
+
 /* Human-readable name of an mq_status value (static storage). */
 const char *mq_status_string(int status);
 

@@ -57,6 +57,10 @@ def load() -> ctypes.CDLL:
     lib.mq_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.bf16_gemm.restype = ci
     lib.bf16_gemm.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, ci, vp]
+    lib.bf16_gemm_ws.restype = ci
+    lib.bf16_gemm_ws.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, i64, ci, vp, i64, vp]
+    lib.mq_bf16_gemm_workspace_bytes.restype = i64
+    lib.mq_bf16_gemm_workspace_bytes.argtypes = [i64, i64, i64]
     lib.mq_mfma_probe.restype = ci
     lib.mq_mfma_probe.argtypes = [vp, ci, vp, ctypes.POINTER(ctypes.c_double)]
     lib.mq_status_string.restype = ctypes.c_char_p

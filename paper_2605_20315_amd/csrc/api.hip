@@ -267,17 +267,34 @@ static int gemm_fp4_entry(const uint8_t *a_codes, const uint8_t *a_scales, const
     return launch_gemm_fp4(g, static_cast<hipStream_t>(stream));
 }
 
+int64_t mq_bf16_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const int ks = gemm_bf16_decode_slabs(M, N, K, INT64_MAX, kMaxComputeUnits);
+    return ks >= 2 ? (int64_t)ks * M * N * 4 : 0;
+}
+
 int bf16_gemm(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw, int64_t M, int64_t N,
               int64_t K, void *y, int64_t ldy, int out, void *stream)
 {
-    if (M < 0 || N < 0 || K <= 0 || K % 8 != 0 || ldx < K || ldw < K) return MQ_ERR_SHAPE;
+    return bf16_gemm_ws(x_bf16, ldx, w_bf16, ldw, M, N, K, y, ldy, out, nullptr, 0, stream);
+}
+
+int bf16_gemm_ws(const void *x_bf16, int64_t ldx, const void *w_bf16, int64_t ldw, int64_t M, int64_t N,
+                 int64_t K, void *y, int64_t ldy, int out, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (M < 0 || N < 0 || K <= 0 || K % 8 != 0 || ldx < K || ldw < K || workspace_bytes < 0) return MQ_ERR_SHAPE;
     if (out != MQ_OUT_BF16 && out != MQ_OUT_FP32) return MQ_ERR_ARG;
     if (M == 0 || N == 0) return MQ_OK;
     if (!x_bf16 || !w_bf16 || !y) return MQ_ERR_NULL;
     int rc = check_out(y, N, ldy, out);
     if (rc != MQ_OK) return rc;
     if (!aligned(x_bf16, 16) || !aligned(w_bf16, 16) || ldx % 8 != 0 || ldw % 8 != 0) return MQ_ERR_ALIGN;
+    if (workspace && !aligned(workspace, 16)) return MQ_ERR_ALIGN;
     GemmArgs g{};
+    g.ws = workspace_bytes > 0 ? static_cast<float *>(workspace) : nullptr;
+    g.ws_bytes = g.ws ? workspace_bytes : 0;
+    g.ksplit = 1;
     g.a = x_bf16;
     g.b = w_bf16;
     g.lda = ldx;

@@ -26,7 +26,9 @@
 //                       tiles loaded from global memory straight into LDS.
 //   gemm_bf16_pipelined the BF16 baseline on smaller problems, same LDS pipeline, tiles staged
 //                       through registers.
-//   bf16_skinny_kernel  BF16 with M <= 64 (decode shapes), weight streaming.
+//   bf16_skinny_kernel  BF16 with M <= 64 (decode shapes), weight streaming, K split over the waves.
+//   bf16_decode_kernel  BF16 with 17 <= M <= 64, weight streaming, N split over the waves, the
+//                       activations shared through LDS, K slabs across workgroups with a workspace.
 //   gemm_simple_kernel  any K % 16 == 0 / K % 8 == 0 that the tiled kernels do not take.
 //
 // The LDS pipeline (the BF16 kernels): block tile BM x BN x 64, two LDS stages, and the
@@ -642,8 +644,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs g)
     const int64_t slab_quads = g.M * g.N / 4;
     f32x4 sum = p[0];
     for (int sl = 1; sl < g.ksplit; ++sl) sum += p[sl * slab_quads];
-    const float scale = (*g.a_alpha) * (*g.b_alpha);
-    sum *= scale;
+    if (g.a_alpha) sum *= (*g.a_alpha) * (*g.b_alpha);  // NVFP4: the two tensor-level scales; BF16: none
     if constexpr (OUT_BF16) {
         typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
         const bf16x4 o = {(__bf16)sum[0], (__bf16)sum[1], (__bf16)sum[2], (__bf16)sum[3]};
@@ -1046,6 +1047,178 @@ __global__ __launch_bounds__(512) void bf16_skinny_kernel(GemmArgs g)
         }
 }
 
+// ---- decode batches of 17 .. 64 tokens: weight streaming with the activations shared through LDS ---
+
+// Above 16 tokens the kernel above is bound by its own re-reads of the activations: every
+// workgroup (16 RT rows of W) fetches all of X from L2, which for 64 tokens is four times the
+// weight traffic at RT = 1.  Here the eight waves of a workgroup split N instead of K (16 rows of
+// W each, 128 per workgroup) and share one copy of X: per 128-wide K super-step the workgroup
+// loads the [16 MT, 128] slice of X once, through registers into a double-buffered LDS tile (rows
+// padded by 16 bytes: the 16 rows a quarter-wave reads then fall on different banks), and every
+// wave reads its MFMA fragments from there; W goes from global memory to registers, 64 contiguous
+// bytes per lane and super-step, four super-steps ahead.  X then costs 1/8 of the weight traffic
+// per token tile.  A narrow N (N = 4096: 32 workgroups) is made up for by K slabs across
+// workgroups when the caller passes a workspace: a work item is (slab, row group), partial sums go
+// to ws[slab][M][N] and splitk_reduce_kernel adds them in ascending order.  Lane roles as above:
+// row r = lane % 16 of the wave's 16 W rows (or of a token tile), group g = lane / 16 holds the
+// 32 k values [32 g, 32 g + 32) of a super-step; accumulator i: W row 4 g + i, token lane % 16.
+template <int MT, bool OUT_BF16>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void bf16_decode_kernel(GemmArgs g,
+                                                                                                  int row_groups)
+{
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int XROW = 256 + 16;                 // bytes per X row in LDS (128 BF16 + padding)
+    constexpr int XBUF = MT * 16 * XROW;           // one buffer
+    constexpr int XCH = MT * 16 * 16 / 512;        // 16-byte chunks of the X slice per thread: MT / 2 (MT even)
+    static_assert(MT == 2 || MT == 4, "token tiles in pairs: the X slice is loaded by 512 threads");
+    static_assert(XCH == 1 || XCH == 2, "one or two 16-byte chunks of X per thread and super-step");
+    __shared__ __attribute__((aligned(16))) char xl[2 * XBUF];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = lane & 15, grp = lane >> 4;
+    const int rg = (int)(blockIdx.x % row_groups), slab = (int)(blockIdx.x / row_groups);
+    const int64_t n0 = (int64_t)rg * 128 + wave * 16;
+    const int S = (int)(g.K / 128);
+    const int SL = (S + g.ksplit - 1) / g.ksplit;
+    const int s0 = slab * SL < S ? slab * SL : S, s1 = s0 + SL < S ? s0 + SL : S;
+
+    int64_t wr = n0 + row;
+    wr = wr < g.N ? wr : g.N - 1;
+    const uint4 *wp = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.b) + wr * g.ldb + grp * 32);
+    // this thread's chunks of the X slice: chunk c = tid + 512 u -> token c / 16, bytes 16 (c % 16) of the 256
+    const uint4 *xg[XCH];
+    int xdst[XCH];
+#pragma unroll
+    for (int u = 0; u < XCH; ++u) {
+        const int c = tid + 512 * u;
+        int64_t tok = c >> 4;
+        xdst[u] = (int)tok * XROW + (c & 15) * 16;
+        tok = tok < g.M ? tok : g.M - 1;
+        xg[u] = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(g.a) + tok * g.lda) + (c & 15);
+    }
+    // Register rings, four super-steps deep: slot of X(st) and of W(st) = (st - s0) % 4.  The X ring
+    // is a set of named registers (as an array the compiler moved it to LDS and waited for every
+    // load right after issuing it); the W ring is indexed by compile-time constants only.
+    uint4 xa0, xa1, xa2, xa3, xb0, xb1, xb2, xb3, wq[4][4];
+    xb0 = xb1 = xb2 = xb3 = make_uint4(0, 0, 0, 0);
+    auto load_x = [&](int st, uint4 &ra, uint4 &rb) __attribute__((always_inline)) {
+        st = st < S ? st : S - 1;
+        ra = xg[0][st * 16];
+        if constexpr (XCH > 1) rb = xg[XCH - 1][st * 16];
+    };
+    auto store_x = [&](auto bufc, const uint4 &ra, const uint4 &rb) __attribute__((always_inline)) {
+        constexpr int B = decltype(bufc)::value;
+        *reinterpret_cast<uint4 *>(xl + B * XBUF + xdst[0]) = ra;
+        if constexpr (XCH > 1) *reinterpret_cast<uint4 *>(xl + B * XBUF + xdst[XCH - 1]) = rb;
+    };
+    auto load_w = [&](int st, auto slot) __attribute__((always_inline)) {
+        constexpr int Q = decltype(slot)::value;
+        st = st < S ? st : S - 1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wq[Q][j] = wp[st * 16 + j];
+    };
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    // all fragment reads of a super-step are issued before its first MFMA (one LDS round trip per
+    // step instead of one per MFMA), and the MT accumulation chains are interleaved
+    auto compute = [&](auto bufc, auto slot) __attribute__((always_inline)) {
+        constexpr int B = decltype(bufc)::value, Q = decltype(slot)::value;
+        uint4 xf[MT][4];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const char *xrow = xl + B * XBUF + (t * 16 + row) * XROW + grp * 64;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xf[t][j] = *reinterpret_cast<const uint4 *>(xrow + j * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wq[Q][j]),
+                                                                 __builtin_bit_cast(bf16x8, xf[t][j]), acc[t], 0, 0, 0);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+
+    // prologue: X(s0) into buffer 0; X(s0 + 1 .. s0 + 4) and W(s0 .. s0 + 3) in registers
+    // (issue order pinned: the load counter is in order, and what the loop may leave in flight
+    // follows from the order here)
+    load_x(s0, xa0, xb0);
+    load_w(s0, I0{});
+    __builtin_amdgcn_sched_barrier(0);
+    load_x(s0 + 1, xa1, xb1);
+    load_w(s0 + 1, I1{});
+    __builtin_amdgcn_sched_barrier(0);
+    load_x(s0 + 2, xa2, xb2);
+    load_w(s0 + 2, I2{});
+    __builtin_amdgcn_sched_barrier(0);
+    load_x(s0 + 3, xa3, xb3);
+    load_w(s0 + 3, I3{});
+    __builtin_amdgcn_sched_barrier(0);
+    store_x(I0{}, xa0, xb0);
+    load_x(s0 + 4, xa0, xb0);
+    __builtin_amdgcn_sched_barrier(0);
+    // __syncthreads() would also wait for every global load in flight (it drains the vector-memory
+    // counter), i.e. expose the full HBM latency once per super-step; the barrier here only waits
+    // for this wave's LDS traffic.  The loads return into registers that the compiler tracks itself.
+    auto lds_barrier = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+    lds_barrier();
+    // Super-step st computes from buffer (st - s0) % 2; meanwhile X(st + 1) goes from registers into
+    // the other buffer (everybody left it before the barrier that ended step st - 1), and the
+    // registers just used are refilled four super-steps ahead, X(st + 5) and W(st + 4).  The
+    // hardware counts returning loads in issue order, so a value is only waited for together
+    // with everything issued before it: X, which comes from L2, is therefore fetched as far ahead
+    // as W, or every step would wait for all of the weights in flight.  One barrier per step.
+#define MQ_DECODE_STEP(ST, U, BUF, XA, XB)                                       \
+    if ((ST) < s1) compute(std::integral_constant<int, BUF>{}, U{}); /* uniform */ \
+    store_x(std::integral_constant<int, (BUF) ^ 1>{}, XA, XB);       /* X(st + 1) */ \
+    load_x((ST) + 5, XA, XB);                                                    \
+    load_w((ST) + 4, U{});                                                       \
+    lds_barrier();                                                               \
+    __builtin_amdgcn_sched_barrier(0);
+    for (int st = s0; st < s1; st += 4) {
+        MQ_DECODE_STEP(st, I0, 0, xa1, xb1)
+        MQ_DECODE_STEP(st + 1, I1, 1, xa2, xb2)
+        MQ_DECODE_STEP(st + 2, I2, 0, xa3, xb3)
+        MQ_DECODE_STEP(st + 3, I3, 1, xa0, xb0)
+    }
+#undef MQ_DECODE_STEP
+
+    // accumulator i: W row 4 * grp + i, token lane % 16
+    const int64_t n = n0 + 4 * grp;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int64_t m = t * 16 + row;
+        if (m >= g.M || n >= g.N) continue;
+        if (g.ksplit > 1) {  // unscaled partial sums of this slab (N % 4 == 0 here)
+            *reinterpret_cast<f32x4 *>(g.ws + ((int64_t)slab * g.M + m) * g.N + n) = acc[t];
+            continue;
+        }
+        using T = std::conditional_t<OUT_BF16, __bf16, float>;
+        T *dst = static_cast<T *>(g.y) + m * g.ldy + n;
+        if (n + 3 < g.N) {
+            if constexpr (OUT_BF16) {
+                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                *reinterpret_cast<bf16x4 *>(dst) =
+                    bf16x4{(__bf16)acc[t][0], (__bf16)acc[t][1], (__bf16)acc[t][2], (__bf16)acc[t][3]};
+            } else {
+                *reinterpret_cast<f32x4 *>(dst) = acc[t];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (n + i < g.N) dst[i] = (T)acc[t][i];
+        }
+    }
+}
+
 // ---- fallback for K not a multiple of 64: one thread per output, exact products ---------------
 
 __device__ __forceinline__ float e2m1_f32(uint32_t c)
@@ -1221,12 +1394,38 @@ int launch_skinny(const GemmArgs &g, hipStream_t s)
     return note_launch(hipGetLastError());
 }
 
+// 17 .. 64 tokens with K % 128 == 0 and the row stride rules of the decode kernel.
+template <bool OUT_BF16>
+int launch_decode(const GemmArgs &g0, hipStream_t s, int slabs)
+{
+    GemmArgs g = g0;
+    g.ksplit = slabs;
+    const int64_t row_groups = (g.N + 127) / 128;
+    if (row_groups * slabs > 0x7FFFFFFF) return MQ_ERR_SHAPE;
+    const dim3 grid((unsigned)(row_groups * slabs)), block(512);
+    if (g.M <= 32)
+        bf16_decode_kernel<2, OUT_BF16><<<grid, block, 0, s>>>(g, (int)row_groups);
+    else
+        bf16_decode_kernel<4, OUT_BF16><<<grid, block, 0, s>>>(g, (int)row_groups);
+    int rc = note_launch(hipGetLastError());
+    if (rc != MQ_OK || slabs == 1) return rc;
+    const int64_t quads = g.M * (g.N / 4);
+    splitk_reduce_kernel<OUT_BF16><<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s>>>(g);
+    return note_launch(hipGetLastError());
+}
+
 template <bool FP4, bool OUT_BF16>
 int launch_any(const GemmArgs &g, hipStream_t s)
 {
     if (g.M == 0 || g.N == 0) return MQ_OK;
     if constexpr (!FP4) {
         // decode shapes: a few tokens against the whole weight matrix
+        if (g.M > 16 && g.M <= 64 && g.K % 128 == 0) {
+            int cus = 0;
+            if (int rc = compute_units(cus)) return rc;
+            const int slabs = gemm_bf16_decode_slabs(g.M, g.N, g.K, g.ws ? g.ws_bytes : 0, cus);
+            if (slabs > 0) return launch_decode<OUT_BF16>(g, s, slabs);
+        }
         if (g.M <= 64 && g.K % 128 == 0 && (g.N + 15) / 16 <= 0x7FFFFFFF) return launch_skinny<OUT_BF16>(g, s);
     }
     // The tiled kernels step K by 64.
@@ -1326,6 +1525,29 @@ SmallPlan gemm_fp4_small_plan(int64_t M, int64_t N, int64_t K, int64_t ws_bytes,
         if (ks >= 2 && kt * (ks - 1) > 9 * waves * ks) plan.slabs = (int)ks;
     }
     return plan;
+}
+
+// K slabs for the decode-batch BF16 kernel (17 .. 64 tokens), given this much workspace; 0: the
+// kernel does not serve the problem, 1: no slabs.  Measured on N = 4096 .. 28672 (us per launch,
+// this kernel / the K-split kernel above): a wide N (at least CUs/2 row groups of 128) needs no
+// slabs: gate_up 41.5 / 69.5 at 64 tokens, 38.3 / 51.1 at 32.  A narrow N needs slabs, i.e. a
+// workspace and a second pass of about 5 us, which pays above 32 tokens with a long K (down,
+// K = 14336: 42.6 / 63.4 at 64 tokens, 40.7 / 51.6 at 48) and not otherwise (K = 4096 at 48 tokens:
+// o 16.1 / 17.0 but qkv 26.1 / 21.6; o at 32 tokens 14.5 / 13.3).  Slabs fill about two workgroups
+// per compute unit, keep at least four 128-wide super-steps each, and keep the partial sums'
+// traffic (8 bytes per output and slab) below half of the weights'.
+int gemm_bf16_decode_slabs(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus)
+{
+    if (M <= 16 || M > 64 || N <= 0 || K <= 0 || K % 128 != 0) return 0;
+    const int64_t groups = (N + 127) / 128, steps = K / 128;
+    if (2 * groups >= cus) return 1;
+    if (M <= 32 || K < 8192 || ws_bytes <= 0 || N % 4 != 0) return 0;
+    int64_t ks = 2 * cus / groups;
+    if (ks > steps / 4) ks = steps / 4;
+    if (ks > K / (8 * M)) ks = K / (8 * M);
+    if (ks > ws_bytes / (M * N * 4)) ks = ws_bytes / (M * N * 4);
+    if (ks < 2 || 2 * groups * ks < cus) return 0;  // too few workgroups even so
+    return (int)ks;
 }
 
 int launch_mfma_probe(float *out, int iters, int blocks, hipStream_t s)

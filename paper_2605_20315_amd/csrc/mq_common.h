@@ -69,6 +69,8 @@ struct SmallPlan {
     int slabs;
 };
 SmallPlan gemm_fp4_small_plan(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
+// K slabs of the decode-batch BF16 kernel (17 .. 64 tokens) given this much workspace; 0: not served by it
+int gemm_bf16_decode_slabs(int64_t M, int64_t N, int64_t K, int64_t ws_bytes, int cus);
 // sets the dynamic-LDS limit of every tiled kernel on the current device (idempotent)
 int configure_gemm_kernels();
 int launch_gemm_fp4(const GemmArgs &g, hipStream_t s);

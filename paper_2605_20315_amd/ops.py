@@ -223,6 +223,34 @@ def bf16_gemm(x_bf16: torch.Tensor, w_bf16: torch.Tensor, out: int = MQ_OUT_BF16
     return y
 
 
+def mq_bf16_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    """Workspace size that lets bf16_gemm_ws choose its K slabs freely (0: it would use none)."""
+    return int(_lib.load().mq_bf16_gemm_workspace_bytes(M, N, K))
+
+
+def bf16_gemm_ws(x_bf16: torch.Tensor, w_bf16: torch.Tensor, workspace: torch.Tensor | None,
+                 out: int = MQ_OUT_BF16, y: torch.Tensor | None = None) -> torch.Tensor:
+    """bf16_gemm with a caller-owned workspace (any contiguous GPU tensor, or None) for the partial
+    sums of decode batches."""
+    _need_gpu(x_bf16, w_bf16)
+    assert x_bf16.dtype == torch.bfloat16 and w_bf16.dtype == torch.bfloat16
+    M, K, ldx = _rows_k_ld(x_bf16)
+    N, K2, ldw = _rows_k_ld(w_bf16)
+    assert K == K2
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.bfloat16 if out == MQ_OUT_BF16 else torch.float32,
+                        device=x_bf16.device)
+    ldy = y.stride(0) if M > 1 else max(y.stride(0), N)
+    ws_ptr, ws_bytes = 0, 0
+    if workspace is not None:
+        assert workspace.is_cuda and workspace.is_contiguous()
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    rc = _lib.load().bf16_gemm_ws(x_bf16.data_ptr(), ldx, w_bf16.data_ptr(), ldw, M, N, K,
+                                  y.data_ptr(), ldy, out, ws_ptr, ws_bytes, _stream())
+    _lib.check(rc, "bf16_gemm_ws")
+    return y
+
+
 def nvfp4_linear(x_bf16: torch.Tensor, alpha_x: torch.Tensor, w_codes, w_scales, alpha_w,
                  out: int = MQ_OUT_BF16, y: torch.Tensor | None = None, codes=None, scales=None,
                  layout: int = MQ_LAYOUT_LINEAR, workspace: torch.Tensor | None = None):

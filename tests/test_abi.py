@@ -85,6 +85,9 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.bf16_gemm(None, 64, None, 64, 4, 4, 64, None, 8, 0, None) == 1
     assert lib.bf16_gemm(None, 32, None, 64, 4, 4, 64, None, 8, 0, None) == 2
     assert lib.nvfp4_global_scale(None, 4, 64, 64, None, None) == 1
+    assert lib.bf16_gemm_ws(None, 64, None, 64, 4, 4, 64, None, 8, 0, None, 0, None) == 1
+    assert lib.bf16_gemm_ws(None, 64, None, 64, 4, 4, 64, None, 8, 0, None, -1, None) == 2
+    assert lib.bf16_gemm_ws(None, 64, None, 64, 0, 4, 64, None, 8, 0, None, 0, None) == 0
 
 
 def test_workspace_size_query(lib):
