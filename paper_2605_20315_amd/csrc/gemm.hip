@@ -111,7 +111,7 @@ __device__ __forceinline__ void tile_of(int wg, int tiles_m, int tiles_n, int &t
 // instructions, and now and then an LDS write / a global load.  Nothing moves across a phase
 // boundary: in particular no consumer of a global load is hoisted towards the load, which would
 // turn the prefetch distance into a stall.
-template <int MFMAS, int READS, int VALU_PER, int WRITES, int VMEMS>
+template <int MFMAS, int READS, int VALU_PER, int WRITES, int VMEMS, int SALUS = 0>
 __device__ __forceinline__ void sched_phase()
 {
 #pragma unroll
@@ -122,6 +122,7 @@ __device__ __forceinline__ void sched_phase()
         if (WRITES > 0 && (i % (MFMAS / WRITES)) == (MFMAS / WRITES) - 1)
             __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                 // DS write
         if (VMEMS > 0 && i < VMEMS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+        if (SALUS > 0 && i < SALUS) __builtin_amdgcn_sched_group_barrier(0x004, 1, 0);  // SALU
     }
     __builtin_amdgcn_sched_barrier(0);
 }
@@ -141,14 +142,51 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, f32x16 (&acc)[C::TM]
         char *const base = static_cast<char *>(g.y) + (mw * g.ldy + nw) * (int64_t)sizeof(T);
         const uint32_t lane_off = (uint32_t)((4 * fhalf) * g.ldy + frow) * (uint32_t)sizeof(T);
         const int64_t row_bytes = g.ldy * (int64_t)sizeof(T);
+        // A wave alone on its SIMD executes a chain of dependent instructions at about 8 cycles
+        // each, so the values of two output rows go through scaling, rounding and the stores
+        // stage by stage (the empty asm statements keep the stages apart), not value by value:
+        // measured 5.1 us per 128x128 tile for the value-by-value order.  BF16: one conversion
+        // packs the values of rows r and r + 1, stored as the low and the high half.
 #pragma unroll
         for (int i = I0; i < I0 + NI; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < 16; r += 2) {
                 char *const rowp = base + (int64_t)(i * 32 + 8 * (r / 4) + (r % 4)) * row_bytes;
+                float v[2][C::TN];
+                // (read as AGPRs where they are: copies made through plain assignments let the
+                // compiler move the whole accumulator set to VGPRs and scratch at the loop exit)
 #pragma unroll
-                for (int j = 0; j < C::TN; ++j)
-                    *reinterpret_cast<T *>(rowp + (uint64_t)lane_off + j * 32 * sizeof(T)) = (T)(acc[i][j][r] * scale);
+                for (int j = 0; j < C::TN; ++j) {
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[0][j]) : "a"(acc[i][j][r]));
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[1][j]) : "a"(acc[i][j][r + 1]));
+                }
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) v[0][j] *= scale, v[1][j] *= scale;
+#pragma unroll
+                for (int j = 0; j < C::TN; ++j) asm volatile("" : "+v"(v[0][j]), "+v"(v[1][j]));
+                if constexpr (OUT_BF16) {
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    uint32_t ob[C::TN];
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j)
+                        ob[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{v[0][j], v[1][j]}, bf16x2));
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j) asm volatile("" : "+v"(ob[j]));
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j) {
+                        char *const pj = rowp + (uint64_t)lane_off + j * 32 * sizeof(T);
+                        *reinterpret_cast<uint16_t *>(pj) = (uint16_t)ob[j];
+                        *reinterpret_cast<uint16_t *>(pj + row_bytes) = (uint16_t)(ob[j] >> 16);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < C::TN; ++j) {
+                        char *const pj = rowp + (uint64_t)lane_off + j * 32 * sizeof(T);
+                        *reinterpret_cast<float *>(pj) = v[0][j];
+                        *reinterpret_cast<float *>(pj + row_bytes) = v[1][j];
+                    }
+                }
             }
         return;
     }
@@ -160,7 +198,9 @@ __device__ __forceinline__ void epilogue(const GemmArgs &g, f32x16 (&acc)[C::TM]
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = mw + i * 32 + 8 * (r / 4) + 4 * fhalf + (r % 4);
-                if (m < g.M && n < g.N) static_cast<T *>(g.y)[m * g.ldy + n] = (T)(acc[i][j][r] * scale);
+                float v;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
+                if (m < g.M && n < g.N) static_cast<T *>(g.y)[m * g.ldy + n] = (T)(v * scale);
             }
         }
 }
@@ -222,15 +262,22 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     // The lane offsets are relative to the first row of the wave tile (whose 64-bit address is
     // scalar), so they fit 32 bits for any operand size.
     uint32_t vc[8], vs[8];
-    const char *ta_c, *tb_c, *ta_s, *tb_s;  // first A / B row of this wave's tile: codes, scales
+    // Running pointers to the K step that the next load_tile reads, for the first A / B row of
+    // this wave's tile (codes, scales); they advance by one K step per load and stop at the last
+    // step of K, so the loads issued past the end of a tile re-read that step.  (Advancing costs
+    // a dozen scalar instructions per K step; recomputing base + t * step cost thirty, in one
+    // block in front of the loads.)
+    const char *pa_c, *pb_c, *pa_s, *pb_s;
+    int t_next;
     auto set_tile = [&](int64_t m0, int64_t n0) {
         int64_t ra = m0 + wm0, rb = n0 + wn0;
         ra = ra < g.M ? ra : g.M - 1;
         rb = rb < g.N ? rb : g.N - 1;
-        ta_c = static_cast<const char *>(g.a) + ra * g.a_c_row;
-        tb_c = static_cast<const char *>(g.b) + rb * g.b_c_row;
-        ta_s = reinterpret_cast<const char *>(g.a_scales) + ra * g.a_s_row;
-        tb_s = reinterpret_cast<const char *>(g.b_scales) + rb * g.b_s_row;
+        t_next = k0 < KT ? k0 : KT - 1;
+        pa_c = static_cast<const char *>(g.a) + ra * g.a_c_row + t_next * g.a_c_step;
+        pb_c = static_cast<const char *>(g.b) + rb * g.b_c_row + t_next * g.b_c_step;
+        pa_s = reinterpret_cast<const char *>(g.a_scales) + ra * g.a_s_row + t_next * g.a_s_step;
+        pb_s = reinterpret_cast<const char *>(g.b_scales) + rb * g.b_s_row + t_next * g.b_s_step;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const bool isA = q < 4;
@@ -243,21 +290,23 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         }
     };
     RawTile st[NSETS];
-    auto load_tile = [&](int t, RawTile &r) {
-        t = t < KT ? t : KT - 1;
-        auto rsrc = [](const void *base, int64_t off) {
-            return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(static_cast<const char *>(base)) + off, 0, -1,
-                                                     0x00020000);
+    auto load_tile = [&](RawTile &r) {
+        auto rsrc = [](const char *p) {
+            return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(p), 0, -1, 0x00020000);
         };
-        const __amdgpu_buffer_rsrc_t rac = rsrc(ta_c, (int64_t)t * g.a_c_step), rbc = rsrc(tb_c, (int64_t)t * g.b_c_step);
-        const __amdgpu_buffer_rsrc_t ras = rsrc(ta_s, (int64_t)t * g.a_s_step);
-        const __amdgpu_buffer_rsrc_t rbs = rsrc(tb_s, (int64_t)t * g.b_s_step);
+        const __amdgpu_buffer_rsrc_t rac = rsrc(pa_c), rbc = rsrc(pb_c), ras = rsrc(pa_s), rbs = rsrc(pb_s);
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const u32x4 c = __builtin_amdgcn_raw_buffer_load_b128(q < 4 ? rac : rbc, (int)vc[q], 0, 0);
             r.c[q] = make_uint4(c[0], c[1], c[2], c[3]);
             r.s[q] = __builtin_amdgcn_raw_buffer_load_b32(q < 4 ? ras : rbs, (int)vs[q], 0, 0);
         }
+        const int64_t adv = -(int64_t)(t_next + 1 < KT);  // all ones while a next K step exists (no branch)
+        t_next -= (int)adv;
+        pa_c += g.a_c_step & adv;
+        pb_c += g.b_c_step & adv;
+        pa_s += g.a_s_step & adv;
+        pb_s += g.b_s_step & adv;
     };
     // Scale register of the K step being expanded: sigma*2^-8 as FP16 for block 2h in the low
     // half and for block 2h+1 in the high half (an E4M3 byte shifted left by 7 is that number).
@@ -269,7 +318,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             uint32_t sc = r.s[q];
-            asm volatile("" : "+v"(sc));  // first use of the prefetched register stays here
+            asm("" : "+v"(sc));  // first use of the prefetched register stays here
             sg[q] = __builtin_amdgcn_perm(0u, sc, sel) << 7;
         }
     };
@@ -278,7 +327,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             uint32_t w = p == 0 ? r.c[q].x : p == 1 ? r.c[q].y : p == 2 ? r.c[q].z : r.c[q].w;
-            asm volatile("" : "+v"(w));
+            asm("" : "+v"(w));
             const _Float16 sig = __builtin_bit_cast(_Float16, (uint16_t)(p < 2 ? sg[q] : sg[q] >> 16));
             const f16x2 s = {sig, sig};
             // four conversions, then four multiplies: a multiply issued right behind the
@@ -287,7 +336,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
             f16x2 c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 1);
             f16x2 c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 2);
             f16x2 c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 3);
-            asm volatile("" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
+            asm("" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
             c0 *= s, c1 *= s, c2 *= s, c3 *= s;
             f[q] = make_uint4(__builtin_bit_cast(uint32_t, c0), __builtin_bit_cast(uint32_t, c1),
                               __builtin_bit_cast(uint32_t, c2), __builtin_bit_cast(uint32_t, c3));
@@ -317,7 +366,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         sched_phase<16, 0, 4, 0, 0>();
         prep_scales(nxt, kt + 1 < k1);
         expand_phase(nxt, 0, fr[0]);
-        load_tile(kt + NSETS, cur);
+        load_tile(cur);
         mfmas(fr[1]);
         sched_phase<16, 0, 6, 0, 16>();
     };
@@ -330,7 +379,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     item_of(tile, tm, tn);
     set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
-    for (int u = 0; u < NSETS; ++u) load_tile(k0 + u, st[u]);
+    for (int u = 0; u < NSETS; ++u) load_tile(st[u]);
     while (true) {
         const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 #pragma unroll
@@ -355,7 +404,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
             item_of(tile, tm, tn);
             set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
-            for (int u = 0; u < NSETS; ++u) load_tile(k0 + u, st[u]);
+            for (int u = 0; u < NSETS; ++u) load_tile(st[u]);
         }
         if constexpr (SPLIT == 1) {
             epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
@@ -543,7 +592,7 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
             uint32_t sc = rs[R][q];
-            asm volatile("" : "+v"(sc));
+            asm("" : "+v"(sc));
             sg[q] = __builtin_amdgcn_perm(0u, sc, sel) << 7;
         }
     };
@@ -553,14 +602,14 @@ __global__ __launch_bounds__(64 * MAXS) void gemm_fp4_small(GemmArgs g, int tile
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
             uint32_t w = p == 0 ? rc[R][q].x : p == 1 ? rc[R][q].y : p == 2 ? rc[R][q].z : rc[R][q].w;
-            asm volatile("" : "+v"(w));
+            asm("" : "+v"(w));
             const _Float16 sig = __builtin_bit_cast(_Float16, (uint16_t)(p < 2 ? sg[q] : sg[q] >> 16));
             const f16x2 sv = {sig, sig};
             f16x2 c0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 0);
             f16x2 c1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 1);
             f16x2 c2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 2);
             f16x2 c3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 256.0f, 3);
-            asm volatile("" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
+            asm("" : "+v"(c0), "+v"(c1), "+v"(c2), "+v"(c3));
             c0 *= sv, c1 *= sv, c2 *= sv, c3 *= sv;
             f[q] = make_uint4(__builtin_bit_cast(uint32_t, c0), __builtin_bit_cast(uint32_t, c1),
                               __builtin_bit_cast(uint32_t, c2), __builtin_bit_cast(uint32_t, c3));
