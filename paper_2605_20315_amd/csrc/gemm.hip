@@ -263,10 +263,10 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     // scalar), so they fit 32 bits for any operand size.
     uint32_t vc[8], vs[8];
     // Running pointers to the K step that the next load_tile reads, for the first A / B row of
-    // this wave's tile (codes, scales); they advance by one K step per load and stop at the last
-    // step of K, so the loads issued past the end of a tile re-read that step.  (Advancing costs
-    // a dozen scalar instructions per K step; recomputing base + t * step cost thirty, in one
-    // block in front of the loads.)
+    // this wave's tile (codes, scales); advance() moves them on by one K step and stops at the
+    // last step of K, so the loads issued past the end of a tile re-read that step.  (Advancing
+    // costs some twenty scalar instructions per K step, placed under the MFMAs of the phase in
+    // front of the loads; recomputing base + t * step cost thirty, in one block at the loads.)
     const char *pa_c, *pb_c, *pa_s, *pb_s;
     int t_next;
     auto set_tile = [&](int64_t m0, int64_t n0) {
@@ -301,6 +301,8 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
             r.c[q] = make_uint4(c[0], c[1], c[2], c[3]);
             r.s[q] = __builtin_amdgcn_raw_buffer_load_b32(q < 4 ? ras : rbs, (int)vs[q], 0, 0);
         }
+    };
+    auto advance = [&]() {
         const int64_t adv = -(int64_t)(t_next + 1 < KT);  // all ones while a next K step exists (no branch)
         t_next -= (int)adv;
         pa_c += g.a_c_step & adv;
@@ -361,9 +363,11 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         expand_phase(cur, 2, fr[0]);
         mfmas(fr[1]);
         sched_phase<16, 0, 4, 0, 0>();
+        // the scalar pointer arithmetic of the loads below, spread under this phase's MFMAs
+        advance();
         expand_phase(cur, 3, fr[1]);
         mfmas(fr[0]);
-        sched_phase<16, 0, 4, 0, 0>();
+        sched_phase<16, 0, 4, 0, 0, 16>();
         prep_scales(nxt, kt + 1 < k1);
         expand_phase(nxt, 0, fr[0]);
         load_tile(cur);
@@ -379,7 +383,10 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     item_of(tile, tm, tn);
     set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
-    for (int u = 0; u < NSETS; ++u) load_tile(st[u]);
+    for (int u = 0; u < NSETS; ++u) {
+        if (u) advance();
+        load_tile(st[u]);
+    }
     while (true) {
         const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 #pragma unroll
@@ -404,7 +411,10 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
             item_of(tile, tm, tn);
             set_tile((int64_t)tm * BM, (int64_t)tn * BN);
 #pragma unroll
-            for (int u = 0; u < NSETS; ++u) load_tile(st[u]);
+            for (int u = 0; u < NSETS; ++u) {
+        if (u) advance();
+        load_tile(st[u]);
+    }
         }
         if constexpr (SPLIT == 1) {
             epilogue<C, OUT_BF16>(g, acc, scale, m0, n0, wm0, wn0, frow, fhalf);
