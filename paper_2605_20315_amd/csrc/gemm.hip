@@ -235,7 +235,7 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     using C = PCfg<256, 256, 2, 2>;  // wave-level constants: 128x128 wave tile, 4x4 MFMA tiles
     static_assert(SPLIT == 1 || SPLIT == 2 || SPLIT == 4, "K is split over 1, 2 or 4 waves");
     constexpr int BM = SPLIT == 4 ? 128 : 256, BN = SPLIT == 1 ? 256 : 128;
-    constexpr int NSETS = 2;  // register sets of prefetched codes (3 measured no faster)
+    constexpr int NSETS = 2;  // register sets of prefetched codes (3, i.e. two K steps of lookahead: no faster)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: the K range depends on it
     const int wm0 = SPLIT == 1 ? (wave >> 1) * 128 : SPLIT == 2 ? (wave & 1) * 128 : 0;
