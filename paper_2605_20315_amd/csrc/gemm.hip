@@ -1509,10 +1509,46 @@ int launch_any(const GemmArgs &g, hipStream_t s)
         const int64_t r1 = (big_tiles + cus - 1) / cus, r2 = (mid_tiles + cus - 1) / cus,
                       r4 = (small_tiles + cus - 1) / cus;
         const int64_t c1 = 100 * r1, c2 = 55 * r2, c4 = 34 * r4;
-        if (2 * mid_tiles < cus || (c4 < c1 && c4 < c2))
-            return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, g, s, cus);
-        if (c2 < c1) return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, g, s, cus);
-        return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, g, s, cus);
+        auto launch_variant = [&](int variant, const GemmArgs &ga) {
+            if (variant == 4) return launch_persistent(gemm_fp4_direct<OUT_BF16, 4>, 128, 128, 128 * 1024, ga, s, cus);
+            if (variant == 2) return launch_persistent(gemm_fp4_direct<OUT_BF16, 2>, 256, 128, 128 * 1024, ga, s, cus);
+            return launch_persistent(gemm_fp4_direct<OUT_BF16, 1>, 256, 256, 0, ga, s, cus);
+        };
+        const int one = (2 * mid_tiles < cus || (c4 < c1 && c4 < c2)) ? 4 : c2 < c1 ? 2 : 1;
+        const int64_t one_cost = one == 4 ? c4 : one == 2 ? c2 : c1;
+        // Two launches instead of one when the tiles leave a ragged last round: the first columns
+        // of N in one shape, the remaining columns in another (M = 2048, N = 28672: 3 rounds of
+        // whole tiles + 16 tile columns as 256x128 tiles cost 3.55 tile times instead of 3.85;
+        // M = 2048, N = 6144: 256x128 tiles on 4096 columns + 128x128 tiles on 2048 cost 0.89
+        // instead of 1).  Rounds are charged as above, the second launch four microseconds in
+        // units of a hundredth of a whole tile's time (0.022 us per K element + 6).
+        auto cost_of = [&](int variant, int64_t n) {
+            const int64_t bm = variant == 4 ? 128 : 256, bn = variant == 1 ? 256 : 128;
+            const int64_t tiles = ((g.M + bm - 1) / bm) * ((n + bn - 1) / bn);
+            return (variant == 1 ? 100 : variant == 2 ? 55 : 34) * ((tiles + cus - 1) / cus);
+        };
+        const int64_t second = (int64_t)(400.0 / (0.022 * (double)g.K + 6.0)) + 1;
+        int64_t best = one_cost, best_n = 0;
+        int best_a = 0, best_b = 0;
+        static const int variants[3] = {1, 2, 4};
+        for (int64_t n = 256; n < g.N; n += 256)
+            for (int va : variants)
+                for (int vb : variants) {
+                    if (va == vb) continue;
+                    const int64_t c = cost_of(va, n) + cost_of(vb, g.N - n) + second;
+                    if (c < best) best = c, best_n = n, best_a = va, best_b = vb;
+                }
+        if (best_n > 0) {
+            GemmArgs ga = g, gb = g;
+            ga.N = best_n;
+            gb.N = g.N - best_n;
+            gb.b = static_cast<const char *>(g.b) + best_n * g.b_c_row;
+            gb.b_scales = g.b_scales + best_n * g.b_s_row;
+            gb.y = static_cast<char *>(g.y) + best_n * (int64_t)(OUT_BF16 ? 2 : 4);
+            if (int rc = launch_variant(best_a, ga)) return rc;
+            return launch_variant(best_b, gb);
+        }
+        return launch_variant(one, g);
     } else {
         // Same choice by rounds of workgroups as above: 256x256 tiles, or 256x128 tiles (half the
         // work per workgroup, somewhat less efficient) when they waste less of the last round;
