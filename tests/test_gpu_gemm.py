@@ -159,6 +159,41 @@ def test_split_k_path_with_ragged_edges(K):
     check_gemm_bf16(host_bits(y[ridx]), oracle.gemm_f64(a, b), oracle.row_norms(a), oracle.row_norms(b))
 
 
+def test_two_column_ranges_in_two_tile_shapes():
+    """M = 2040, N = 6096, K = 4096: 192 tiles of 256x256 would leave a quarter of the compute
+    units idle, so the launcher gives the first 4096 columns to 256x128 tiles with K over wave
+    pairs and the remaining 2000 to 128x128 tiles with K over the four waves (two launches on
+    offset B, scale and output pointers).  Sampled rows, all columns: the seam at column 4096,
+    the ragged last column tile and the guard band behind N must all be right."""
+    rng = np.random.default_rng(77)
+    M, N, K = 2040, 6096, 4096
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    a = oracle.dequantize(ac, asc, 0.5)
+    b = oracle.dequantize(bc, bsc, 0.25)
+    rows = np.unique(np.concatenate([np.arange(0, M, 173), np.arange(M - 40, M), [127, 128, 255, 256, 257, 1023, 1024]]))
+    ref = oracle.gemm_f64(a[rows], b)
+    na, nb = oracle.row_norms(a[rows]), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        ops = [ac, asc, bc, bsc]
+        if layout == mq.MQ_LAYOUT_KTILE:
+            ops[0], ops[1] = to_ktile(ac, asc)
+            ops[2], ops[3] = to_ktile(bc, bsc)
+        d = [dev_u8(v) for v in ops]
+        aa, ba = dev_scalar(0.5), dev_scalar(0.25)
+        ld = N + 24
+        b32 = torch.full((M, ld), -7.0, dtype=torch.float32, device="cuda")
+        b16 = torch.full((M, ld), -7.0, dtype=torch.bfloat16, device="cuda")
+        y32 = mq.nvfp4_gemm(d[0], d[1], aa, d[2], d[3], ba, mq.MQ_OUT_FP32, b32[:, :N], layout=layout)
+        y16 = mq.nvfp4_gemm(d[0], d[1], aa, d[2], d[3], ba, mq.MQ_OUT_BF16, b16[:, :N], layout=layout)
+        torch.cuda.synchronize()
+        check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+        check_gemm_bf16(host_bits(y16[ridx].contiguous()), ref, na, nb)
+        assert torch.equal(y32.to(torch.bfloat16), y16)
+        assert bool((b32[:, N:] == -7.0).all()) and bool((b16[:, N:] == -7.0).all())
+
+
 @pytest.mark.timeout(600)
 def test_operand_larger_than_2_gib():
     """An activation operand of 2.3 GB: K-step and row offsets pass 2^31 in both layouts."""
