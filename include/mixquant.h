@@ -15,8 +15,9 @@
  *  - Return value: MQ_OK, or an mq_status error.  Arguments are validated on the host before
  *    anything is launched: with any status but MQ_ERR_HIP nothing has been enqueued.
  *    MQ_ERR_HIP means the HIP runtime refused a launch (mq_last_hip_error() returns its
- *    hipError_t); an entry point that launches several kernels (nvfp4_global_scale, the
- *    slab-split product) may then have enqueued the earlier ones, and its outputs are undefined.
+ *    hipError_t); an entry point that launches several kernels (nvfp4_global_scale, a product
+ *    cut into K slabs or into two column ranges) may then have enqueued the earlier ones, and
+ *    its outputs are undefined.
  *  - One-time set-up per device (kernel attributes, the address of the static scratch array):
  *    done by mq_init(), or else by the first product on that device.  A caller that captures
  *    streams into HIP graphs calls mq_init() once per device beforehand; after that no entry
