@@ -194,6 +194,41 @@ def test_two_column_ranges_in_two_tile_shapes():
         assert bool((b32[:, N:] == -7.0).all()) and bool((b16[:, N:] == -7.0).all())
 
 
+# (M, N, K): ragged shapes with a long K on both sides of the launcher's choices.  With 256
+# compute units: (1530, 6128, 4096) = 768 columns of 128x128 tiles + 5360 of 256x128 tiles;
+# (3070, 6160, 4096) = 1024 columns of 128x128 + 5136 of 256x256; (3000, 6000, 4608) the same pair
+# at another K; (2500, 9000, 4096) and (3300, 7000, 3072) = 256x128 + 256x256; (1300, 12000, 4096)
+# = 128x128 + 256x256; (1800, 7360, 4992), (2900, 5008, 4096) one launch of 256x256 tiles;
+# (911, 4128, 4800) of 256x128 tiles; (1190, 1888, 4224) of 128x128 tiles.
+LAUNCH_SHAPES = [(1530, 6128, 4096), (3070, 6160, 4096), (3000, 6000, 4608), (2500, 9000, 4096),
+                 (3300, 7000, 3072), (1300, 12000, 4096), (1800, 7360, 4992), (2900, 5008, 4096),
+                 (911, 4128, 4800), (1190, 1888, 4224)]
+
+
+@pytest.mark.parametrize("M,N,K", LAUNCH_SHAPES)
+def test_ragged_shapes_across_launch_paths(M, N, K):
+    """One tile shape or two column ranges in two shapes: sampled rows (tile seams, the ragged
+    tail), all columns, both layouts, both output types."""
+    rng = np.random.default_rng([M, N, K])
+    print(f"\n[case] launch paths M={M} N={N} K={K}", flush=True)
+    ac, asc = _rand_nvfp4(rng, M, K)
+    bc, bsc = _rand_nvfp4(rng, N, K)
+    a = oracle.dequantize(ac, asc, 0.5)
+    b = oracle.dequantize(bc, bsc, 0.25)
+    seams = np.arange(128, M, 128)
+    rows = np.unique(np.concatenate([seams - 1, seams, rng.integers(0, M, 24), [0, M - 2, M - 1]]))
+    rows = rows[(rows >= 0) & (rows < M)]
+    ref = oracle.gemm_f64(a[rows], b)
+    na, nb = oracle.row_norms(a[rows]), oracle.row_norms(b)
+    ridx = torch.from_numpy(rows).cuda()
+    for layout in (mq.MQ_LAYOUT_LINEAR, mq.MQ_LAYOUT_KTILE):
+        y32 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_FP32, layout)
+        check_gemm_fp32(y32[ridx].cpu().numpy(), ref, na, nb)
+        y16 = _gpu_gemm(ac, asc, 0.5, bc, bsc, 0.25, mq.MQ_OUT_BF16, layout)
+        check_gemm_bf16(host_bits(y16[ridx]), ref, na, nb)
+        assert torch.equal(y32.to(torch.bfloat16), y16)
+
+
 @pytest.mark.timeout(600)
 def test_operand_larger_than_2_gib():
     """An activation operand of 2.3 GB: K-step and row offsets pass 2^31 in both layouts."""
