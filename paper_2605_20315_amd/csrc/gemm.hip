@@ -325,9 +325,11 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         }
     };
     uint4 fr[2][8];
-    auto expand_phase = [&](const RawTile &r, int p, uint4(&f)[8]) {
+    // q0 .. q1-1: the operand tiles to expand (0..3 = A row tiles, 4..7 = B row tiles)
+    auto expand_phase = [&](const RawTile &r, int p, uint4(&f)[8], int q0 = 0, int q1 = 8) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
+            if (q < q0 || q >= q1) continue;
             uint32_t w = p == 0 ? r.c[q].x : p == 1 ? r.c[q].y : p == 2 ? r.c[q].z : r.c[q].w;
             asm("" : "+v"(w));
             const _Float16 sig = __builtin_bit_cast(_Float16, (uint16_t)(p < 2 ? sg[q] : sg[q] >> 16));
@@ -361,9 +363,14 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
     auto kstep = [&](int kt, auto rr) {
         constexpr int R = decltype(rr)::value;
         RawTile &cur = st[R], &nxt = st[(R + 1) % NSETS];
+        // The last two A row tiles of this step's first phase are expanded here, right before
+        // the MFMAs that use them (the ninth onwards), not in the load phase of the previous K
+        // step, which is the one phase that fills the wave's issue slots (+0.5-1 %; three tiles
+        // deferred: no better).
+        expand_phase(cur, 0, fr[0], 2, 4);
         expand_phase(cur, 1, fr[1]);
         mfmas(fr[0]);
-        sched_phase<16, 0, 4, 0, 0>();
+        sched_phase<16, 0, 5, 0, 0>();
         expand_phase(cur, 2, fr[0]);
         mfmas(fr[1]);
         sched_phase<16, 0, 4, 0, 0>();
@@ -377,10 +384,11 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
         // fills the wave's issue slots, and a wait is an instruction like any other: +0.5-0.8 %).
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         prep_scales(nxt, kt + 1 < k1);
-        expand_phase(nxt, 0, fr[0]);
+        expand_phase(nxt, 0, fr[0], 0, 2);
+        expand_phase(nxt, 0, fr[0], 4, 8);
         load_tile(cur);
         mfmas(fr[1]);
-        sched_phase<16, 0, 6, 0, 16>();
+        sched_phase<16, 0, 5, 0, 16>();
     };
 
     // Persistent workgroups: tile ids blockIdx.x, blockIdx.x + gridDim.x, ...  The first loads of
@@ -404,7 +412,8 @@ __global__ __launch_bounds__(256) void gemm_fp4_direct(GemmArgs g, int tiles_m, 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
         prep_scales(st[0], k0 < k1);
-        expand_phase(st[0], 0, fr[0]);
+        expand_phase(st[0], 0, fr[0], 0, 2);
+        expand_phase(st[0], 0, fr[0], 4, 8);
         // No separate tail: the loop runs whole groups of NSETS K steps, and a step past the end
         // multiplies by zero scales.  (Peeled tail steps make the compiler shuffle all 256
         // accumulator registers at the control-flow joins.)
